@@ -1,0 +1,148 @@
+/*
+ * zvc.h -- C ABI of the zero-value compression (ZVC) library for AMD gfx950.
+ *
+ * ZVC (paper section 5.1, "Zero-value compression"): a tensor is treated as a
+ * flat run of n elements of w bytes each.  Every 32 consecutive elements form
+ * one group described by a 32-bit presence mask (bit b set <=> element
+ * 32*g + b is non-zero); the non-zero elements are kept, in order, and zeros
+ * are dropped.  Decompression (section 5.2, decompression engine) walks the
+ * mask bits and puts back either the next kept element or a zero.  The scheme
+ * is lossless.
+ *
+ * Compressed stream layout used by every entry point here:
+ *
+ *     [ masks : G = ceil(n/32) little-endian uint32 ][ values : nnz * w bytes ]
+ *
+ *   - bit 0 (LSB) of a mask is the first element of its group; bits that fall
+ *     past n in the last group are 0;
+ *   - "zero" means the all-zero bit pattern of the w-byte element: -0.0, NaN
+ *     and denormals are non-zero and are kept bit for bit;
+ *   - compressed_bytes = 4*G + w*nnz.  Bytes of the output buffer past that
+ *     are unspecified.
+ *   The paper appends each group's non-zeros right after its mask; this
+ *   library stores all masks first and all values after them.  The byte count
+ *   is identical; the planar order lets both parts be written coalesced.
+ *
+ * Conventions for every function:
+ *   - `w` is the element width in bytes, 2 or 4 (anything else: ZVC_E_WIDTH).
+ *     The element type is irrelevant (fp32, fp16, bf16, int: all w-byte words).
+ *   - pointers named d_* are DEVICE pointers, h_* are HOST pointers.  The
+ *     caller owns every buffer; the library allocates no device memory and
+ *     keeps no pointer after the call's work has completed.
+ *   - d_in / d_out of the uncompressed tensor must be aligned to w bytes; the
+ *     compressed buffer must be aligned to 4 bytes.  16-byte alignment of the
+ *     uncompressed tensor selects the fast kernels; anything less still works.
+ *   - input and output ranges must not overlap.
+ *   - device work is enqueued on the given stream and the call returns
+ *     without waiting for it (zvc_offload is the one exception, see there).
+ *   - n = 0 is legal.
+ *   - arguments are validated on the host before any GPU call; a non-OK status
+ *     means nothing was enqueued (ZVC_E_HIP excepted: a HIP call failed and
+ *     earlier work of this call may already be enqueued).
+ *   - a workspace serves one call at a time: calls that use the same workspace
+ *     must be ordered (same stream, or event dependencies).  Its contents
+ *     between calls are private to the library.
+ */
+#ifndef ZVC_H_
+#define ZVC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum zvc_status {
+    ZVC_OK = 0,
+    ZVC_E_ARG = 1,       /* null pointer, overlapping or otherwise invalid argument */
+    ZVC_E_WIDTH = 2,     /* w is not 2 or 4 */
+    ZVC_E_CAPACITY = 3,  /* an output buffer is smaller than the required bound */
+    ZVC_E_WORKSPACE = 4, /* workspace smaller than zvc_workspace_bytes(n, w) */
+    ZVC_E_ALIGN = 5,     /* pointer not aligned as required */
+    ZVC_E_HIP = 6,       /* a HIP runtime call failed */
+    ZVC_E_CORRUPT = 7    /* a compressed stream is inconsistent with its stated size */
+} zvc_status;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* zvc_status_string(zvc_status st);
+
+/* ---- pure host arithmetic (no GPU needed) -------------------------------- */
+
+/* 4 * ceil(n/32): bytes of the mask part (section 5.1: one 32-bit mask per 32
+ * elements). */
+size_t zvc_mask_bytes(size_t n);
+
+/* Worst-case compressed size 4*ceil(n/32) + w*n (every element non-zero: the
+ * 1-bit-per-element metadata overhead of section 5.1).  0 for a bad w. */
+size_t zvc_max_compressed_bytes(size_t n, int w);
+
+/* Bytes of device workspace needed by the calls below for n elements of width
+ * w.  0 for a bad w.  The workspace must be 256-byte aligned. */
+size_t zvc_workspace_bytes(size_t n, int w);
+
+/* Host-side consistency check of a compressed stream held in HOST memory:
+ * ZVC_OK iff bytes == 4*G + w * (sum of popcounts of the G masks) and the last
+ * mask has no bit set past n.  (The decoder of section 5.2 consumes exactly
+ * popcount(mask) words per group, so any other size is a damaged stream.) */
+zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w);
+
+/* ---- device entry points -------------------------------------------------- */
+
+/* Prepare a freshly allocated workspace (fills it with its initial state).
+ * Call once per allocation before its first use; ws is the allocation's size
+ * in bytes, at least zvc_workspace_bytes(0, 4). */
+zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream);
+
+/* Count-only pass: *d_bytes = 4*ceil(n/32) + w*nnz, the size zvc_compress would
+ * report (section 5.4: the compressed copy returns the compressed size).
+ * d_bytes is an 8-byte aligned device word, valid when `stream` reaches the end
+ * of this call's work. */
+zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_bytes,
+                               void* d_ws, size_t ws, hipStream_t stream);
+
+/* Compress n elements at d_in into d_out (section 5.1; encoder pipeline of
+ * section 5.2: zero test, prefix sum of the mask bits, shift non-zeros to
+ * their packed slots, append).  out_cap is the capacity of d_out in bytes and
+ * must be at least zvc_max_compressed_bytes(n, w) (else ZVC_E_CAPACITY; the
+ * kernel never writes past the bound).  *d_bytes (device, 8-byte aligned)
+ * receives the compressed size. */
+zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                        uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream);
+
+/* Decompress a stream produced by zvc_compress back into n elements at d_out
+ * (section 5.2, decompression engine: popcount of the mask gives the words a
+ * span consumes, a prefix sum gives each slot's source, slots take a stored
+ * word or zero).  comp_bytes is the number of readable bytes at d_comp (at
+ * least zvc_mask_bytes(n)); the kernel never reads past it: if damaged masks
+ * ask for more values than are there, the missing elements decode as zero. */
+zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,
+                          void* d_ws, size_t ws, hipStream_t stream);
+
+/* Offload (section 3 and section 5.4: the activation map leaves GPU memory as
+ * a compressed copy whose size is known on completion).  Compresses d_in into
+ * the device staging buffer d_stage on `compute`, waits ON THE HOST for the
+ * 8-byte size (the one host wait in this library), stores it in *h_bytes, then
+ * enqueues the device-to-host copy of exactly that many bytes into h_pinned on
+ * `copy` (ordered after the compression).  h_pinned should be pinned host
+ * memory for the copy to be asynchronous; h_cap must be at least
+ * zvc_max_compressed_bytes(n, w).  The data in h_pinned is complete when
+ * `copy` has drained; d_stage may be reused only after that. */
+zvc_status zvc_offload(const void* d_in, size_t n, int w, void* d_stage, size_t stage_cap,
+                       void* h_pinned, size_t h_cap, uint64_t* h_bytes, void* d_ws, size_t ws,
+                       hipStream_t compute, hipStream_t copy);
+
+/* Prefetch, the mirror of zvc_offload: enqueues the host-to-device copy of
+ * `bytes` bytes from h_pinned into d_stage on `copy`, then the decompression
+ * into d_out on `compute`, ordered after the copy.  No host wait. */
+zvc_status zvc_prefetch(const void* h_pinned, uint64_t bytes, size_t n, int w, void* d_stage,
+                        size_t stage_cap, void* d_out, void* d_ws, size_t ws, hipStream_t copy,
+                        hipStream_t compute);
+
+#ifdef __cplusplus
+} /* extern "C" */
+#endif
+
+#endif /* ZVC_H_ */

@@ -1,0 +1,116 @@
+"""ctypes binding of the C++ ZVC oracle (oracle/zvc_ref.cpp).
+
+TEST INFRASTRUCTURE ONLY: marshals numpy buffers into the oracle's extern "C"
+functions.  It holds none of the method's arithmetic and imports nothing from
+the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Optional, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_U64 = ctypes.c_uint64
+_BAD = (1 << 64) - 1
+_lib_cache = {}
+
+
+def load(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load (building first if needed) the oracle library and set signatures."""
+    path = path or _build.ensure_built()
+    if path in _lib_cache:
+        return _lib_cache[path]
+    lib = ctypes.CDLL(path)
+    vp, ip = ctypes.c_void_p, ctypes.c_int
+    lib.zvc_ref_groups.restype = _U64
+    lib.zvc_ref_groups.argtypes = [_U64]
+    lib.zvc_ref_compress.restype = _U64
+    lib.zvc_ref_compress.argtypes = [vp, _U64, ip, vp, vp]
+    lib.zvc_ref_compressed_bytes.restype = _U64
+    lib.zvc_ref_compressed_bytes.argtypes = [_U64, ip, _U64]
+    lib.zvc_ref_compress_stream.restype = _U64
+    lib.zvc_ref_compress_stream.argtypes = [vp, _U64, ip, vp]
+    lib.zvc_ref_decompress.restype = _U64
+    lib.zvc_ref_decompress.argtypes = [vp, vp, _U64, ip, vp]
+    lib.zvc_ref_decompress_stream.restype = _U64
+    lib.zvc_ref_decompress_stream.argtypes = [vp, _U64, ip, vp]
+    lib.zvc_ref_count_nonzero.restype = _U64
+    lib.zvc_ref_count_nonzero.argtypes = [vp, _U64, ip]
+    _lib_cache[path] = lib
+    return lib
+
+
+def _as_bytes(a: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    return a.reshape(-1).view(np.uint8)
+
+
+def _ptr(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def groups(n: int, lib=None) -> int:
+    return int((lib or load()).zvc_ref_groups(n))
+
+
+def compressed_bytes(n: int, w: int, nnz: int, lib=None) -> int:
+    return int((lib or load()).zvc_ref_compressed_bytes(n, w, nnz))
+
+
+def compress(x: np.ndarray, w: int, lib=None) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Encode the raw bytes of `x` as n = x.nbytes // w elements.
+
+    Returns (masks uint32[G], values uint8[w * nnz], nnz).
+    """
+    lib = lib or load()
+    raw = _as_bytes(x)
+    n = raw.size // w
+    masks = np.zeros(groups(n, lib), dtype=np.uint32)
+    values = np.zeros(max(n * w, 1), dtype=np.uint8)
+    nnz = lib.zvc_ref_compress(_ptr(raw), n, w, _ptr(masks), _ptr(values))
+    if nnz == _BAD:
+        raise ValueError("unsupported element width %r" % (w,))
+    return masks, values[: nnz * w].copy(), int(nnz)
+
+
+def compress_stream(x: np.ndarray, w: int, lib=None) -> np.ndarray:
+    """Encode into the serialised [masks][values] byte stream (exact length)."""
+    lib = lib or load()
+    raw = _as_bytes(x)
+    n = raw.size // w
+    out = np.zeros(4 * groups(n, lib) + n * w + 1, dtype=np.uint8)
+    used = lib.zvc_ref_compress_stream(_ptr(raw), n, w, _ptr(out))
+    if used == _BAD:
+        raise ValueError("unsupported element width %r" % (w,))
+    return out[:used].copy()
+
+
+def decompress(masks: np.ndarray, values: np.ndarray, n: int, w: int, lib=None) -> np.ndarray:
+    """Decode to a uint8 array of n * w bytes."""
+    lib = lib or load()
+    masks = np.ascontiguousarray(masks, dtype=np.uint32)
+    vals = _as_bytes(values) if values.size else np.zeros(1, dtype=np.uint8)
+    out = np.full(max(n * w, 1), 0xAB, dtype=np.uint8)
+    used = lib.zvc_ref_decompress(_ptr(masks), _ptr(vals), n, w, _ptr(out))
+    if used == _BAD:
+        raise ValueError("unsupported element width %r" % (w,))
+    return out[: n * w]
+
+
+def decompress_stream(stream: np.ndarray, n: int, w: int, lib=None) -> np.ndarray:
+    lib = lib or load()
+    comp = _as_bytes(stream) if stream.size else np.zeros(1, dtype=np.uint8)
+    out = np.full(max(n * w, 1), 0xAB, dtype=np.uint8)
+    used = lib.zvc_ref_decompress_stream(_ptr(comp), n, w, _ptr(out))
+    if used == _BAD:
+        raise ValueError("unsupported element width %r" % (w,))
+    return out[: n * w]
+
+
+def count_nonzero(x: np.ndarray, w: int, lib=None) -> int:
+    lib = lib or load()
+    raw = _as_bytes(x)
+    return int(lib.zvc_ref_count_nonzero(_ptr(raw), raw.size // w, w))
