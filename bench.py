@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the ZVC hot path on one MI355X.
+
+One "step" is one pass of the whole path over one tensor that is already
+resident in HBM: zvc_compress (zero test, masks, per-tile counts, device-wide
+scan, compaction, size) followed by zvc_decompress (mask scan, expand) of the
+result.  `value` counts the uncompressed bytes that go through the codec per
+second: each step pushes n*w bytes through compression and n*w bytes through
+decompression, so value = 2*n*w / step time (the per-direction rates are
+reported beside it).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+
+Prints ONE JSON line.  Only one GPU is used; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+WORKLOADS = ("conv_small", "conv1_style", "sweep_0.05", "sweep_0.2", "sweep_0.5", "sweep_0.8",
+             "sweep_1.0", "layout_fp32_nchw", "layout_fp32_nhwc", "layout_fp32_chwn",
+             "layout_fp16_nchw", "layout_bf16_nchw")
+
+
+def make_workload(name: str, seed: int, device):
+    from paper_1705_01626_amd import workloads
+    if name == "conv_small":
+        return workloads.conv_small(seed, device), "fp32 NCHW 8x64x56x56, relu(N(mu,1)), 40% non-zero"
+    if name == "conv1_style":
+        return (workloads.conv1_style(seed, device),
+                "fp32 NCHW 256x96x55x55 conv1-style, per-channel density U[0.1,0.9], blurred-field support")
+    if name.startswith("sweep_"):
+        d = float(name.split("_")[1])
+        return (workloads.density_sweep(d, seed, device),
+                "fp32 NCHW 64x64x224x224, iid Bernoulli(%.2f) support" % d)
+    if name.startswith("layout_"):
+        key = name[len("layout_"):]
+        return (workloads.layout_variants(seed, device)[key],
+                "128x256x28x28 blurred-field 30%% density, %s" % key)
+    raise SystemExit("unknown workload %r (choose from %s)" % (name, ", ".join(WORKLOADS)))
+
+
+def event_timed(fn, reps: int, torch) -> float:
+    """Average milliseconds per call of `fn` over `reps` back-to-back launches,
+    measured with HIP events recorded on the stream the kernels run on."""
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(reps):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / reps
+
+
+def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0):
+    """The oracle as it stands, single thread, on the same bytes: whole-tensor
+    compress + decompress round trips until about `budget_s` seconds are spent."""
+    import numpy as np
+    from oracle import zvc_ref
+    lib = zvc_ref.load()
+    groups = (n + 31) // 32
+    comp = np.zeros(4 * groups + n * w + 16, dtype=np.uint8)
+    back = np.zeros(n * w + 16, dtype=np.uint8)
+    vp = ctypes.c_void_p
+    reps, spent, best = 0, 0.0, None
+    while reps < 1 or (spent < budget_s and reps < 50):
+        t0 = time.perf_counter()
+        lib.zvc_ref_compress_stream(vp(host_bytes.ctypes.data), n, w, vp(comp.ctypes.data))
+        lib.zvc_ref_decompress_stream(vp(comp.ctypes.data), n, w, vp(back.ctypes.data))
+        dt = time.perf_counter() - t0
+        spent += dt
+        reps += 1
+        best = dt if best is None else min(best, dt)
+    assert np.array_equal(back[: n * w], host_bytes[: n * w])
+    return {"value": round(2.0 * n * w / best / 1e9, 4), "unit": "GB/s", "cores": 1,
+            "kind": "oracle",
+            "sample": "whole tensor (%d bytes), %d compress+decompress round trips, best" % (n * w, reps)}
+
+
+def load_traffic(workload: str):
+    """HBM bytes per launch from committed rocprofv3 counter runs, if recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        table = json.load(f)
+    return table.get(workload)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="conv1_style")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-verify", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the hot path is single-GPU; "
+              "see DESIGN.md for how it would shard); --gpus %d is refused" % args.gpus,
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1705_01626_amd import zvc
+
+    zvc.load()  # fails loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    x, described = make_workload(args.workload, args.seed, dev)
+    n, w = x.numel(), x.element_size()
+    ws = zvc.new_workspace(n, w, dev)
+    comp = zvc.new_compressed_buffer(n, w, dev)
+    d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
+    out = torch.empty_like(x)
+
+    zvc.zvc_compress(x, comp, d_bytes, ws)
+    nbytes = int(d_bytes.item())
+    groups = (n + 31) // 32
+    nnz = (nbytes - 4 * groups) // w
+    density = nnz / n
+
+    def compress():
+        zvc.zvc_compress(x, comp, d_bytes, ws)
+
+    def decompress():
+        zvc.zvc_decompress(comp, nbytes, out, ws)
+
+    def step():
+        compress()
+        decompress()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # per-kernel durations with HIP events on the launch stream
+    ms_c = event_timed(compress, args.steps, torch)
+    ms_d = event_timed(decompress, args.steps, torch)
+    torch.cuda.synchronize()
+
+    if not args.no_verify:
+        assert torch.equal(out.view(torch.uint8), x.view(torch.uint8)), "round trip differs"
+        assert int(d_bytes.item()) == nbytes
+
+    uncompressed = n * w
+    algorithmic = uncompressed + nbytes  # compress: read n*w, write stream; decompress: the mirror
+    dominant, ms_dom = ("zvc_compress", ms_c) if ms_c >= ms_d else ("zvc_decompress", ms_d)
+    achieved = algorithmic / (ms_dom * 1e-3) / 1e9
+    traffic = load_traffic(args.workload)
+    result = {
+        "metric": "ZVC compress+decompress GB/s (uncompressed bytes) and % of HBM peak",
+        "value": round(2.0 * uncompressed / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32" if w == 4 else "u16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "tensor": described, "elements": n,
+                   "element_bytes": w, "uncompressed_bytes": uncompressed,
+                   "compressed_bytes": nbytes, "density": round(density, 6),
+                   "compression_ratio": round(uncompressed / nbytes, 4), "seed": args.seed},
+        "compress_GBps": round(uncompressed / (ms_c * 1e-3) / 1e9, 2),
+        "decompress_GBps": round(uncompressed / (ms_d * 1e-3) / 1e9, 2),
+        "compress_ms": round(ms_c, 5),
+        "decompress_ms": round(ms_d, 5),
+        "hbm_peak_fraction": {"compress": round(algorithmic / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                              "decompress": round(algorithmic / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": algorithmic,
+                     "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        host = x.view(torch.uint8).cpu().numpy().reshape(-1)
+        result["cpu_baseline"] = cpu_baseline(host, n, w)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
