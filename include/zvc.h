@@ -89,6 +89,20 @@ size_t zvc_workspace_bytes(size_t n, int w);
  * popcount(mask) words per group, so any other size is a damaged stream.) */
 zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w);
 
+/* ---- scan tuning and diagnostics ------------------------------------------ */
+
+/* The device-wide scan of per-tile counts (the "offset to the next mask" of
+ * section 5.1) lets a tile wait for its predecessors' counts.  After `polls`
+ * fruitless polls the waiting tile computes the missing count itself, so the
+ * wait always ends.  Default 2000 (about a millisecond); 0 makes every wait
+ * help at once, which tests use to exercise that path.  Process-wide. */
+void zvc_set_lookback_patience(unsigned polls);
+
+/* Number of times, during the last compress/decompress call on this workspace,
+ * that a waiting tile computed a predecessor's count itself.  Synchronous
+ * 8-byte device-to-host copy; call it after the stream has drained. */
+zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count);
+
 /* ---- device entry points -------------------------------------------------- */
 
 /* Prepare a freshly allocated workspace (fills it with its initial state).

@@ -13,9 +13,10 @@
 //     prefix sum over mask bits);
 //   * the offset of a tile's first kept element in the packed stream -- the
 //     paper's "offset to the next mask", a serial chain in hardware -- is a
-//     device-wide exclusive scan of per-tile counts done in the same pass with
-//     decoupled look-back over one 64-bit state word per tile;
-//   * kept elements are staged in LDS at their tile-local rank and leave as
+//     device-wide exclusive scan of per-tile counts done in the same pass:
+//     every tile publishes its count, every 64th tile a running prefix, and a
+//     tile adds the counts between the nearest published prefix and itself;
+//   * kept elements are staged by each wave in LDS in packed order and leave as
 //     aligned 16-byte stores; masks leave as one contiguous run per wave.
 //
 // Decompression mirrors it: per-tile popcount of the masks, the same scan, the
@@ -26,6 +27,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
 #include <cstring>
 
@@ -35,50 +37,70 @@ namespace {
 constexpr int kThreads = 256;                 // 4 waves of 64 lanes
 constexpr int kWaveSize = 64;
 constexpr int kWaves = kThreads / kWaveSize;
-constexpr int kLoads = 4;                     // 16-byte loads per lane per tile
-constexpr int kTileBytes = kThreads * 16 * kLoads;  // 16 KB of input per tile
-constexpr size_t kHeaderBytes = 256;          // workspace header, then tile states
+constexpr size_t kHeaderBytes = 256;          // workspace header, then the scan state
+constexpr int kMinLoads = 4;                  // smallest tile: 16 KB (sizes the workspace)
+constexpr int kStageLoads = 4;                // 16-byte loads a wave stages through LDS at a time
+constexpr int kBlockTiles = 64;               // one running prefix is published per 64 tiles
+constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
 
-template <int W>
+// A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
+template <int W, int LOADS>
 struct Geometry {
     static constexpr int kElemsPerLane = 16 / W;                 // per 16-byte load: 4 | 8
     static constexpr int kLanesPerGroup = 32 / kElemsPerLane;    // lanes covering one mask: 8 | 4
     static constexpr int kGroupsPerLoad = kWaveSize / kLanesPerGroup;  // masks per wave-load: 8 | 16
-    static constexpr int kTileElems = kTileBytes / W;            // 4096 | 8192
-    static constexpr int kTileGroups = kTileElems / 32;          // 128 | 256
-    static_assert(kLoads <= kLanesPerGroup, "mask hand-off needs one lane per load");
-    static_assert(kTileGroups <= kThreads, "one thread per mask in the decoder");
+    static constexpr int kTileBytes = kThreads * 16 * LOADS;
+    static constexpr int kTileElems = kTileBytes / W;
+    static constexpr int kTileGroups = kTileElems / 32;
+    // mask hand-off: load j's mask is kept by lane (j % kLanesPerGroup) of the group
+    static constexpr int kMaskRegs = (LOADS + kLanesPerGroup - 1) / kLanesPerGroup;
+    // decoder: masks handled per thread
+    static constexpr int kMasksPerThread = kTileGroups > kThreads ? kTileGroups / kThreads : 1;
+    // per-wave LDS staging buffer: kStageLoads wave-loads plus alignment slack
+    static constexpr int kStageSteps = LOADS / kStageLoads;
+    static constexpr int kWaveStageBytes = kStageLoads * kWaveSize * 16 + 16;
+    static_assert(LOADS % kStageLoads == 0, "tile is staged in whole steps");
 };
 
 // Workspace header.  Lives at the start of the caller's workspace.
 struct WsHeader {
-    unsigned int ticket;           // next tile to hand out
     unsigned int done;             // finished workgroups (count-only pass)
+    unsigned int pad0;
     unsigned long long nnz;        // accumulator of the count-only pass
     unsigned long long size_word;  // compressed size for zvc_offload's read-back
-    unsigned long long pad[29];
+    unsigned long long helped;     // predecessor counts computed by a waiting tile
+    unsigned long long pad[28];
 };
 static_assert(sizeof(WsHeader) == kHeaderBytes, "header is 256 bytes");
 
-// Tile state word: status in the two top bits, a count in the rest.
-constexpr unsigned long long kStatusShift = 62;
-constexpr unsigned long long kStatusInvalid = 0;    // nothing published yet
-constexpr unsigned long long kStatusAggregate = 1;  // value = this tile's own count
-constexpr unsigned long long kStatusPrefix = 2;     // value = count of this and all earlier tiles
-constexpr unsigned long long kValueMask = (1ull << kStatusShift) - 1;
+// Scan state in the workspace, after the header:
+//   counts[t]   : 32-bit word per tile, top bit = published, rest = the tile's
+//                 own count of kept elements;
+//   prefixes[b] : 64-bit word per block of 64 tiles, top bit = published, rest
+//                 = kept elements in all tiles up to and including tile 64b+63.
+constexpr unsigned kCountValid = 0x80000000u;
+constexpr unsigned long long kPrefixValid = 1ull << 63;
 
 __host__ __device__ inline size_t div_up(size_t a, size_t b) { return a / b + (a % b != 0); }
 
-inline size_t tiles_for(size_t n, int w) {
-    const size_t tile_elems = static_cast<size_t>(kTileBytes / w);
+inline size_t tiles_for(size_t n, int w, int loads) {
+    const size_t tile_elems = static_cast<size_t>(kThreads * 16 * loads / w);
     return div_up(n, tile_elems);
+}
+inline size_t counts_bytes(size_t tiles) { return 4 * div_up(tiles, 64) * 64; }   // padded to 256 B
+inline size_t prefixes_bytes(size_t tiles) { return 8 * div_up(tiles, kBlockTiles); }
+inline size_t scan_state_bytes(size_t tiles) {
+    return counts_bytes(tiles) + div_up(prefixes_bytes(tiles), 256) * 256;
 }
 
 // ------------------------------------------------------------ device helpers
-__device__ inline unsigned long long load_state(const unsigned long long* p) {
+__device__ inline unsigned long long load64(const unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ inline void store_state(unsigned long long* p, unsigned long long v) {
+__device__ inline void store64(unsigned long long* p, unsigned long long v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void store32(unsigned* p, unsigned v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -92,6 +114,14 @@ __device__ inline unsigned long long wave_sum(unsigned long long v) {
 #pragma unroll
     for (int off = 1; off < kWaveSize; off <<= 1) v += __shfl_xor(v, off);
     return v;
+}
+
+// LDS written by some lanes of a wave is read by other lanes of the same wave:
+// order the accesses (LDS operations of one wave execute in order).
+__device__ inline void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // 16 bytes of input for the lane whose first element is e0.  Elements at or
@@ -141,130 +171,281 @@ __device__ inline unsigned element_of(const uint4& v, int c) {
     return (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
 }
 
-// Decoupled look-back (single-pass scan): sum of the counts of all tiles
-// before `tile`.  Called by one whole wave.  Lane k inspects predecessor
-// tile-1-k (then 64 further back per round); a predecessor with a prefix ends
-// the walk, aggregates in front of it are added.  Every predecessor holds a
-// ticket taken before ours, so it is resident and will publish.
-__device__ inline unsigned long long look_back(const unsigned long long* states, unsigned tile,
-                                               int lane) {
-    unsigned long long exclusive = 0;
-    long long base = static_cast<long long>(tile) - 1;
-    while (true) {
-        const long long idx = base - lane;
-        // tiles before the first behave as a published prefix of zero
-        unsigned long long st = (kStatusPrefix << kStatusShift);
-        if (idx >= 0) st = load_state(states + idx);
-        const unsigned long long status = st >> kStatusShift;
-        const unsigned long long invalid = __ballot(status == kStatusInvalid);
-        const unsigned long long prefix = __ballot(status == kStatusPrefix);
-        // lanes up to and including the nearest prefix must all be published
-        const int first_prefix = prefix ? __ffsll(static_cast<long long>(prefix)) - 1 : kWaveSize;
-        const unsigned long long needed =
-            first_prefix >= kWaveSize - 1 ? ~0ull : ((2ull << first_prefix) - 1ull);
-        if (invalid & needed) {
-            __builtin_amdgcn_s_sleep(1);
-            continue;
+// Copies LDS bytes [shift, end) to global memory at gbase + same offsets, where
+// gbase is 16-byte aligned: whole 16-byte chunks as one store, the ragged first
+// and last chunk element by element.  Called by one wave.
+template <int W>
+__device__ inline void wave_copy_out(unsigned char* gbase, const unsigned char* stage,
+                                     unsigned shift, unsigned end, int lane) {
+    const unsigned chunks = (end + 15u) / 16u;
+    for (unsigned q = lane; q < chunks; q += kWaveSize) {
+        const unsigned lo = q * 16u, hi = lo + 16u;
+        if (lo >= shift && hi <= end) {
+            *reinterpret_cast<uint4*>(gbase + lo) = *reinterpret_cast<const uint4*>(stage + lo);
+        } else {
+            const unsigned a = lo > shift ? lo : shift;
+            const unsigned b = hi < end ? hi : end;
+            for (unsigned o = a; o < b; o += W) {
+                if (W == 4)
+                    *reinterpret_cast<unsigned*>(gbase + o) =
+                        *reinterpret_cast<const unsigned*>(stage + o);
+                else
+                    *reinterpret_cast<unsigned short*>(gbase + o) =
+                        *reinterpret_cast<const unsigned short*>(stage + o);
+            }
         }
-        const unsigned long long take = (lane <= first_prefix) ? (st & kValueMask) : 0ull;
-        exclusive += wave_sum(take);
-        if (first_prefix < kWaveSize) break;
-        base -= kWaveSize;
     }
+}
+
+// The mirror: global bytes [shift, end) at gbase into LDS at the same offsets;
+// bytes at or past end_valid are not read and become zero.  Called by one wave.
+template <int W>
+__device__ inline void wave_copy_in(unsigned char* stage, const unsigned char* gbase,
+                                    unsigned shift, unsigned end, unsigned end_valid, int lane) {
+    const unsigned chunks = (end + 15u) / 16u;
+    for (unsigned q = lane; q < chunks; q += kWaveSize) {
+        const unsigned lo = q * 16u, hi = lo + 16u;
+        if (lo >= shift && hi <= end_valid) {
+            *reinterpret_cast<uint4*>(stage + lo) = *reinterpret_cast<const uint4*>(gbase + lo);
+        } else {
+            const unsigned a = lo > shift ? lo : shift;
+            const unsigned b = hi < end ? hi : end;
+            for (unsigned o = a; o < b; o += W) {
+                if (W == 4)
+                    *reinterpret_cast<unsigned*>(stage + o) =
+                        o < end_valid ? *reinterpret_cast<const unsigned*>(gbase + o) : 0u;
+                else
+                    *reinterpret_cast<unsigned short*>(stage + o) =
+                        o < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + o)
+                                      : static_cast<unsigned short>(0);
+            }
+        }
+    }
+}
+
+// Device-wide exclusive scan of the per-tile counts, single pass (the paper's
+// "offset to the next mask", section 5.1, for a whole tile at a time).
+// Called by one whole wave of the tile's workgroup.  Returns the number of
+// kept elements in all tiles before `tile`.
+//
+// Protocol.  Every tile publishes its own count.  Tile 64b+63 also publishes
+// the running total up to and including itself (one prefix per block of 64
+// tiles).  A tile finds the nearest published block prefix behind it and adds
+// the counts of the tiles between that block and itself, two counts per 8-byte
+// load across the wave.  In steady state that is a few hundred counts and the
+// walk takes one pass.
+//
+// Why this shape (measured on MI355X): a device-scope load of a line that other
+// XCDs are still writing costs a coherence round trip and slows the streaming
+// traffic around it, while lines that have gone quiet are served from the local
+// L2.  Counts are written once and read afterwards; running prefixes, which are
+// written late, are kept sparse so that few lines are ever read while hot.  A
+// classic look-back that polls a status+value word per tile, or a ticket
+// counter per tile (one same-address atomic costs about 11 ns here), holds the
+// whole kernel to a third of memory speed.
+//
+// Tiles are numbered by workgroup id.  The hardware hands workgroups out in id
+// order, so a predecessor is normally already running and publishes within
+// microseconds.  The wait does not rely on that: after `patience` fruitless
+// polls the waiting wave computes a missing predecessor's count itself
+// (`count_tile`, a re-read of that tile's input) and publishes it, so the walk
+// ends whatever the dispatch order.
+template <class CountTile>
+__device__ inline unsigned long long tile_exclusive_prefix(unsigned* counts,
+                                                           unsigned long long* prefixes,
+                                                           unsigned tile, unsigned count, int lane,
+                                                           unsigned patience, WsHeader* hdr,
+                                                           const CountTile& count_tile) {
+    if (lane == 0) store32(counts + tile, kCountValid | count);
+    unsigned long long exclusive = 0;
+    if (tile != 0) {
+        const long long t = static_cast<long long>(tile);
+        unsigned polls = 0;
+        while (true) {
+            // nearest published block prefix; before block 0 the prefix is 0
+            long long bb = t / kBlockTiles - 1;
+            unsigned long long base = 0;
+            long long lo = 0;
+            while (true) {
+                const long long idx = bb - lane;
+                const unsigned long long pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;
+                const unsigned long long have = __ballot((pv & kPrefixValid) != 0);
+                if (have) {
+                    const int k = __ffsll(static_cast<long long>(have)) - 1;
+                    base = __shfl(pv, k) & ~kPrefixValid;
+                    lo = (bb - k + 1) * kBlockTiles;   // first tile after that block
+                    break;
+                }
+                bb -= kWaveSize;
+            }
+            // counts of tiles lo .. t-1 (lo is a multiple of 64: pairs are 8-byte aligned)
+            unsigned long long sum = 0;
+            long long hole = -1;
+#pragma unroll 1
+            for (long long i = lo + 2 * lane; i < t; i += 2 * kWaveSize) {
+                const unsigned long long pair =
+                    load64(reinterpret_cast<const unsigned long long*>(counts + i));
+                const unsigned c0 = static_cast<unsigned>(pair);
+                const unsigned c1 = static_cast<unsigned>(pair >> 32);
+                if (!(c0 & kCountValid) && hole < 0) hole = i;
+                sum += c0 & ~kCountValid;
+                if (i + 1 < t) {
+                    if (!(c1 & kCountValid) && hole < 0) hole = i + 1;
+                    sum += c1 & ~kCountValid;
+                }
+            }
+            const unsigned long long holes = __ballot(hole >= 0);
+            if (!holes) {
+                exclusive = base + wave_sum(sum);
+                break;
+            }
+            if (polls < patience) {
+                ++polls;
+                __builtin_amdgcn_s_sleep(kPollSleep);
+                continue;
+            }
+            // help one unpublished predecessor, then look again without waiting anew
+            const int hole_lane = __ffsll(static_cast<long long>(holes)) - 1;
+            const long long q = __shfl(hole, hole_lane);
+            const unsigned helped_count = count_tile(static_cast<unsigned>(q), lane);
+            unsigned old = 0;
+            if (lane == 0) {
+                old = atomicMax(counts + q, kCountValid | helped_count);  // same value as the owner's
+                atomicAdd(&hdr->helped, 1ull);
+            }
+            // the atomic has returned, so it has been performed before any lane polls again
+            asm volatile("" : : "v"(old) : "memory");
+        }
+    }
+    if (tile % kBlockTiles == kBlockTiles - 1 && lane == 0)
+        store64(prefixes + tile / kBlockTiles, kPrefixValid | (exclusive + count));
     return exclusive;
 }
 
-// Publishes this tile's count, finds the count of all earlier tiles, publishes
-// the inclusive prefix.  Called by wave 0 of the workgroup.
-__device__ inline unsigned long long tile_exclusive_prefix(unsigned long long* states,
-                                                           unsigned tile, unsigned tile_total,
-                                                           int lane) {
-    unsigned long long exclusive = 0;
-    if (tile == 0) {
-        if (lane == 0) store_state(states, (kStatusPrefix << kStatusShift) | tile_total);
-    } else {
-        if (lane == 0)
-            store_state(states + tile, (kStatusAggregate << kStatusShift) | tile_total);
-        exclusive = look_back(states, tile, lane);
-        if (lane == 0)
-            store_state(states + tile, (kStatusPrefix << kStatusShift) | (exclusive + tile_total));
+// Count of non-zero elements of input tile q, by one wave (scan self-help).
+template <int W, int LOADS, bool ALIGNED>
+struct CountInputTile {
+    const unsigned char* in;
+    size_t n;
+    __device__ unsigned operator()(unsigned q, int lane) const {
+        constexpr int E = 16 / W;
+        constexpr int kTileElems = kThreads * LOADS * E;
+        const size_t e0 = static_cast<size_t>(q) * kTileElems;
+        unsigned long long count = 0;
+#pragma unroll 1
+        for (int i = 0; i < LOADS * kWaves; ++i) {
+            const uint4 v = load_chunk<W, ALIGNED>(
+                in, e0 + (static_cast<size_t>(i) * kWaveSize + lane) * E, n);
+            count += __popc(presence_bits<W>(v));
+        }
+        return static_cast<unsigned>(wave_sum(count));
     }
-    return exclusive;
-}
+};
+
+// Count of set mask bits of tile q, by one wave (scan self-help, decoder).
+struct CountMaskTile {
+    const unsigned* masks;
+    size_t num_groups;
+    unsigned tail;        // n % 32
+    int tile_groups;
+    __device__ unsigned operator()(unsigned q, int lane) const {
+        unsigned long long count = 0;
+#pragma unroll 1
+        for (int gi = lane; gi < tile_groups; gi += kWaveSize) {
+            const size_t g = static_cast<size_t>(q) * tile_groups + gi;
+            if (g < num_groups) {
+                unsigned m = masks[g];
+                if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;
+                count += __popc(m);
+            }
+        }
+        return static_cast<unsigned>(wave_sum(count));
+    }
+};
 
 // ------------------------------------------------------------------- kernels
 
-// Puts the workspace header and the first `slots` tile states back to zero.
-__global__ void reset_kernel(unsigned long long* ws_words, size_t header_words, size_t slots) {
-    const size_t total = header_words + slots;
-    for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < total;
+// Zeroes the workspace header and scan state (`words` 8-byte words).
+__global__ void reset_kernel(unsigned long long* ws_words, size_t words) {
+    for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < words;
          i += static_cast<size_t>(gridDim.x) * blockDim.x)
         ws_words[i] = 0ull;
 }
 
 __global__ void write_word_kernel(unsigned long long* dst, unsigned long long v) { *dst = v; }
 
-// Section 5.1 encoder.  One workgroup per tile, tiles handed out by ticket.
-template <int W, bool ALIGNED>
+// Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.
+template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void compress_kernel(
     const unsigned char* __restrict__ in, size_t n, unsigned* __restrict__ masks,
-    unsigned char* __restrict__ values, WsHeader* hdr, unsigned long long* states,
-    unsigned long long* d_bytes, unsigned num_tiles, size_t num_groups) {
-    using G = Geometry<W>;
+    unsigned char* __restrict__ values, WsHeader* hdr, unsigned* counts,
+    unsigned long long* prefixes, unsigned long long* d_bytes, unsigned num_tiles,
+    size_t num_groups, unsigned patience) {
+    using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
+    constexpr int kBitWords = (LOADS * E + 31) / 32;
 
-    __shared__ __align__(16) unsigned char s_stage[kTileBytes + 16];
-    __shared__ unsigned s_tile;
+    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kWaveStageBytes];
     __shared__ unsigned s_wave_total[kWaves];
     __shared__ unsigned long long s_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid / kWaveSize;
-
-    if (tid == 0) s_tile = atomicAdd(&hdr->ticket, 1u);
-    __syncthreads();
-    const unsigned tile = s_tile;
+    const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
 
     // ---- load, zero test, in-wave ranks, masks
-    uint4 data[kLoads];
-    unsigned bits[kLoads];
-    unsigned rank[kLoads];   // wave-local packed position of the lane's first kept element
-    unsigned running = 0;    // wave-uniform: kept elements of earlier loads of this wave
-    unsigned my_mask = 0;
+    uint4 data[LOADS];
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j) {
+        const size_t e0 =
+            tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
+        data[j] = load_chunk<W, ALIGNED>(in, e0, n);
+    }
+    unsigned bit_words[kBitWords];   // the lane's presence bits, E per load
+    unsigned below16[LOADS / 2];     // kept elements of lower lanes in the same load, 16 bits each
+    unsigned run[LOADS + 1];         // wave-uniform: kept elements of the wave's earlier loads
+    unsigned my_mask[G::kMaskRegs];
+#pragma unroll
+    for (int k = 0; k < kBitWords; ++k) bit_words[k] = 0;
+#pragma unroll
+    for (int k = 0; k < LOADS / 2; ++k) below16[k] = 0;
+    run[0] = 0;
     const int lane_in_group = lane % LPG;
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-        const size_t e0 =
-            tile_elem0 + (static_cast<size_t>(wave * kLoads + j) * kWaveSize + lane) * E;
-        data[j] = load_chunk<W, ALIGNED>(in, e0, n);
-        bits[j] = presence_bits<W>(data[j]);
+    for (int j = 0; j < LOADS; ++j) {
+        const unsigned bits = presence_bits<W>(data[j]);
         unsigned below = 0, load_total = 0;
 #pragma unroll
         for (int c = 0; c < E; ++c) {
-            const unsigned long long b = __ballot((bits[j] >> c) & 1u);
+            const unsigned long long b = __ballot((bits >> c) & 1u);
             below += lanes_below(b);
             load_total += static_cast<unsigned>(__popcll(b));
         }
-        rank[j] = running + below;
-        running += load_total;
+        bit_words[(j * E) / 32] |= bits << ((j * E) % 32);
+        below16[j / 2] |= below << (16 * (j % 2));
+        run[j + 1] = run[j] + load_total;
         // the group's mask: OR of the lanes' bit fields, each at its position
-        unsigned m = bits[j] << (E * lane_in_group);
+        unsigned m = bits << (E * lane_in_group);
 #pragma unroll
         for (int off = 1; off < LPG; off <<= 1) m |= __shfl_xor(m, off);
-        if (lane_in_group == j) my_mask = m;
+        if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
     }
-    if (lane_in_group < kLoads) {
-        const size_t g = static_cast<size_t>(tile) * G::kTileGroups +
-                         static_cast<size_t>(wave * kLoads + lane_in_group) * G::kGroupsPerLoad +
-                         lane / LPG;
-        if (g < num_groups) masks[g] = my_mask;
+#pragma unroll
+    for (int q = 0; q < G::kMaskRegs; ++q) {
+        const int j = q * LPG + lane_in_group;  // the load whose mask this lane kept
+        if (j < LOADS) {
+            const size_t g = static_cast<size_t>(tile) * G::kTileGroups +
+                             static_cast<size_t>(wave * LOADS + j) * G::kGroupsPerLoad +
+                             lane / LPG;
+            if (g < num_groups) masks[g] = my_mask[q];
+        }
     }
 
     // ---- tile-level scan of the wave totals
-    if (lane == 0) s_wave_total[wave] = running;
+    if (lane == 0) s_wave_total[wave] = run[LOADS];
     __syncthreads();
     unsigned wave_offset = 0, tile_total = 0;
 #pragma unroll
@@ -274,56 +455,49 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
         tile_total += t;
     }
 
-    // ---- device-wide exclusive scan (decoupled look-back), wave 0
+    // ---- device-wide exclusive scan, wave 0
     if (wave == 0) {
-        const unsigned long long ex = tile_exclusive_prefix(states, tile, tile_total, lane);
+        const CountInputTile<W, LOADS, ALIGNED> count_tile{in, n};
+        const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, tile, tile_total,
+                                                            lane, patience, hdr, count_tile);
         if (lane == 0) s_prefix = ex;
     }
     __syncthreads();
     const unsigned long long exclusive = s_prefix;
 
-    // ---- stage kept elements in LDS.  LDS byte p corresponds to global byte
-    //      (dst - shift) + p, so 16-byte chunks are aligned on both sides.
-    unsigned char* dst = values + exclusive * W;
-    const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
+    // ---- compaction (section 5.2: shift non-zeros to their packed slots).
+    //      Each wave stages kStageLoads loads at a time in its own LDS slice at
+    //      the elements' packed order, then copies the run out.  LDS byte p of
+    //      the slice corresponds to global byte (dst - shift) + p, so 16-byte
+    //      chunks are aligned on both sides.
+    unsigned char* stage = s_stage[wave];
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-        unsigned r = wave_offset + rank[j];
+    for (int h = 0; h < G::kStageSteps; ++h) {
+        const unsigned first_rank = run[h * kStageLoads];
+        const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
+        unsigned char* dst = values + (exclusive + wave_offset + first_rank) * W;
+        const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
 #pragma unroll
-        for (int c = 0; c < E; ++c) {
-            if ((bits[j] >> c) & 1u) {
-                const unsigned v = element_of<W>(data[j], c);
-                if (W == 4)
-                    *reinterpret_cast<unsigned*>(s_stage + shift + r * 4u) = v;
-                else
-                    *reinterpret_cast<unsigned short*>(s_stage + shift + r * 2u) =
-                        static_cast<unsigned short>(v);
-                ++r;
+        for (int jj = 0; jj < kStageLoads; ++jj) {
+            const int j = h * kStageLoads + jj;
+            unsigned r = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
+            const unsigned bits = bit_words[(j * E) / 32] >> ((j * E) % 32);
+#pragma unroll
+            for (int c = 0; c < E; ++c) {
+                if ((bits >> c) & 1u) {
+                    const unsigned v = element_of<W>(data[j], c);
+                    if (W == 4)
+                        *reinterpret_cast<unsigned*>(stage + shift + r * 4u) = v;
+                    else
+                        *reinterpret_cast<unsigned short*>(stage + shift + r * 2u) =
+                            static_cast<unsigned short>(v);
+                    ++r;
+                }
             }
         }
-    }
-    __syncthreads();
-
-    // ---- copy out: whole 16-byte chunks, ragged ends element by element
-    const unsigned end = shift + tile_total * W;
-    const unsigned chunks = (end + 15u) / 16u;
-    unsigned char* gbase = dst - shift;
-    for (unsigned q = tid; q < chunks; q += kThreads) {
-        const unsigned lo = q * 16u, hi = lo + 16u;
-        if (lo >= shift && hi <= end) {
-            *reinterpret_cast<uint4*>(gbase + lo) = *reinterpret_cast<const uint4*>(s_stage + lo);
-        } else {
-            const unsigned a = lo > shift ? lo : shift;
-            const unsigned b = hi < end ? hi : end;
-            for (unsigned o = a; o < b; o += W) {
-                if (W == 4)
-                    *reinterpret_cast<unsigned*>(gbase + o) =
-                        *reinterpret_cast<const unsigned*>(s_stage + o);
-                else
-                    *reinterpret_cast<unsigned short*>(gbase + o) =
-                        *reinterpret_cast<const unsigned short*>(s_stage + o);
-            }
-        }
+        wave_lds_sync();
+        wave_copy_out<W>(dst - shift, stage, shift, shift + step_total * W, lane);
+        wave_lds_sync();
     }
 
     // ---- section 5.4: the compressed size, reported by the last tile
@@ -333,40 +507,44 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
 
 // Section 5.2 decoder.  values_avail = number of stored elements that may be
 // read; anything the masks ask for beyond it decodes as zero.
-template <int W, bool ALIGNED>
+template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out, WsHeader* hdr,
-    unsigned long long* states, size_t num_groups) {
-    using G = Geometry<W>;
+    unsigned* counts, unsigned long long* prefixes, size_t num_groups, unsigned patience) {
+    using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
+    constexpr int MPT = G::kMasksPerThread;
+    constexpr int kStepGroups = kStageLoads * G::kGroupsPerLoad;  // masks per wave staging step
 
-    __shared__ __align__(16) unsigned char s_stage[kTileBytes + 16];
+    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kWaveStageBytes];
     __shared__ unsigned s_mask[G::kTileGroups];
-    __shared__ unsigned s_group_offset[G::kTileGroups];
-    __shared__ unsigned s_tile;
+    __shared__ unsigned s_group_offset[G::kTileGroups + 1];  // last entry = tile total
     __shared__ unsigned s_wave_total[kWaves];
     __shared__ unsigned long long s_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid / kWaveSize;
-
-    if (tid == 0) s_tile = atomicAdd(&hdr->ticket, 1u);
-    __syncthreads();
-    const unsigned tile = s_tile;
+    const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
 
-    // ---- one thread per mask: popcount, exclusive scan over the tile
-    unsigned m = 0;
-    const size_t g = static_cast<size_t>(tile) * G::kTileGroups + tid;
-    if (tid < G::kTileGroups && g < num_groups) {
-        m = masks[g];
-        const unsigned tail = static_cast<unsigned>(n % 32);
-        if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;  // bits past n never count
+    // ---- MPT consecutive masks per thread: popcount, exclusive scan over the tile
+    unsigned m[MPT];
+    unsigned cnt = 0;
+    const unsigned tail = static_cast<unsigned>(n % 32);
+#pragma unroll
+    for (int k = 0; k < MPT; ++k) {
+        const int gi = tid * MPT + k;
+        const size_t g = static_cast<size_t>(tile) * G::kTileGroups + gi;
+        m[k] = 0;
+        if (gi < G::kTileGroups && g < num_groups) {
+            m[k] = masks[g];
+            if (g == num_groups - 1 && tail != 0) m[k] &= (1u << tail) - 1u;  // bits past n never count
+        }
+        cnt += __popc(m[k]);
     }
-    const unsigned cnt = __popc(m);
     unsigned incl = cnt;
 #pragma unroll
     for (int off = 1; off < kWaveSize; off <<= 1) {
@@ -382,87 +560,86 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
         if (v < wave) wave_offset += t;
         tile_total += t;
     }
-    if (tid < G::kTileGroups) {
-        s_mask[tid] = m;
-        s_group_offset[tid] = wave_offset + incl - cnt;
+    {
+        unsigned off = wave_offset + incl - cnt;
+#pragma unroll
+        for (int k = 0; k < MPT; ++k) {
+            const int gi = tid * MPT + k;
+            if (gi < G::kTileGroups) {
+                s_mask[gi] = m[k];
+                s_group_offset[gi] = off;
+            }
+            off += __popc(m[k]);
+        }
+        if (tid == 0) s_group_offset[G::kTileGroups] = tile_total;
     }
 
     if (wave == 0) {
-        const unsigned long long ex = tile_exclusive_prefix(states, tile, tile_total, lane);
+        const CountMaskTile count_tile{masks, num_groups, tail, G::kTileGroups};
+        const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, tile, tile_total,
+                                                            lane, patience, hdr, count_tile);
         if (lane == 0) s_prefix = ex;
     }
     __syncthreads();
     const unsigned long long exclusive = s_prefix;
 
-    // ---- stage the tile's stored elements in LDS (aligned 16-byte chunks,
-    //      ragged ends element by element, nothing past values_avail)
-    const unsigned char* src = values + exclusive * W;
-    const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
-    unsigned long long readable = values_avail > exclusive ? values_avail - exclusive : 0ull;
-    if (readable > tile_total) readable = tile_total;
-    const unsigned end = shift + tile_total * W;
-    const unsigned end_valid = shift + static_cast<unsigned>(readable) * W;
-    const unsigned chunks = (end + 15u) / 16u;
-    const unsigned char* gbase = src - shift;
-    for (unsigned q = tid; q < chunks; q += kThreads) {
-        const unsigned lo = q * 16u, hi = lo + 16u;
-        if (lo >= shift && hi <= end_valid) {
-            *reinterpret_cast<uint4*>(s_stage + lo) = *reinterpret_cast<const uint4*>(gbase + lo);
-        } else {
-            const unsigned a = lo > shift ? lo : shift;
-            const unsigned b = hi < end ? hi : end;
-            for (unsigned o = a; o < b; o += W) {
-                if (W == 4)
-                    *reinterpret_cast<unsigned*>(s_stage + o) =
-                        o < end_valid ? *reinterpret_cast<const unsigned*>(gbase + o) : 0u;
-                else
-                    *reinterpret_cast<unsigned short*>(s_stage + o) =
-                        o < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + o)
-                                      : static_cast<unsigned short>(0);
-            }
-        }
-    }
-    __syncthreads();
-
-    // ---- expand: each lane rebuilds 16 bytes of output per load
+    // ---- expand (section 5.2: payload words or zeros muxed into place).  Each
+    //      wave stages the stored elements of kStageLoads loads' worth of output
+    //      in its LDS slice, then every lane rebuilds 16 bytes per load.
+    unsigned char* stage = s_stage[wave];
 #pragma unroll
-    for (int j = 0; j < kLoads; ++j) {
-        const int seg = wave * kLoads + j;
-        const size_t e0 = tile_elem0 + (static_cast<size_t>(seg) * kWaveSize + lane) * E;
-        if (e0 >= n) continue;
-        const int gi = seg * G::kGroupsPerLoad + lane / LPG;
-        const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
-        const unsigned gm = s_mask[gi];
-        unsigned r = s_group_offset[gi] + __popc(gm & ((1u << bit0) - 1u));
-        const unsigned field = gm >> bit0;
-        unsigned d[4] = {0u, 0u, 0u, 0u};
+    for (int h = 0; h < G::kStageSteps; ++h) {
+        const int g0 = (wave * LOADS + h * kStageLoads) * G::kGroupsPerLoad;
+        const unsigned first_rank = s_group_offset[g0];
+        const unsigned step_total = s_group_offset[g0 + kStepGroups] - first_rank;
+        const unsigned long long step_begin = exclusive + first_rank;
+        const unsigned char* src = values + step_begin * W;
+        const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
+        unsigned long long readable = values_avail > step_begin ? values_avail - step_begin : 0ull;
+        if (readable > step_total) readable = step_total;
+        wave_copy_in<W>(stage, src - shift, shift, shift + step_total * W,
+                        shift + static_cast<unsigned>(readable) * W, lane);
+        wave_lds_sync();
 #pragma unroll
-        for (int c = 0; c < E; ++c) {
-            if ((field >> c) & 1u) {
-                if (W == 4) {
-                    d[c] = *reinterpret_cast<const unsigned*>(s_stage + shift + r * 4u);
-                } else {
-                    const unsigned v =
-                        *reinterpret_cast<const unsigned short*>(s_stage + shift + r * 2u);
-                    d[c >> 1] |= v << (16 * (c & 1));
-                }
-                ++r;
-            }
-        }
-        if (ALIGNED && e0 + E <= n) {
-            *reinterpret_cast<uint4*>(out + e0 * W) = make_uint4(d[0], d[1], d[2], d[3]);
-        } else {
+        for (int jj = 0; jj < kStageLoads; ++jj) {
+            const int seg = wave * LOADS + h * kStageLoads + jj;
+            const size_t e0 = tile_elem0 + (static_cast<size_t>(seg) * kWaveSize + lane) * E;
+            if (e0 >= n) continue;
+            const int gi = seg * G::kGroupsPerLoad + lane / LPG;
+            const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
+            const unsigned gm = s_mask[gi];
+            unsigned r = s_group_offset[gi] - first_rank + __popc(gm & ((1u << bit0) - 1u));
+            const unsigned field = gm >> bit0;
+            unsigned d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int c = 0; c < E; ++c) {
-                if (e0 + c < n) {
-                    if (W == 4)
-                        reinterpret_cast<unsigned*>(out)[e0 + c] = d[c];
-                    else
-                        reinterpret_cast<unsigned short*>(out)[e0 + c] =
-                            static_cast<unsigned short>((d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
+                if ((field >> c) & 1u) {
+                    if (W == 4) {
+                        d[c] = *reinterpret_cast<const unsigned*>(stage + shift + r * 4u);
+                    } else {
+                        const unsigned v =
+                            *reinterpret_cast<const unsigned short*>(stage + shift + r * 2u);
+                        d[c >> 1] |= v << (16 * (c & 1));
+                    }
+                    ++r;
+                }
+            }
+            if (ALIGNED && e0 + E <= n) {
+                *reinterpret_cast<uint4*>(out + e0 * W) = make_uint4(d[0], d[1], d[2], d[3]);
+            } else {
+#pragma unroll
+                for (int c = 0; c < E; ++c) {
+                    if (e0 + c < n) {
+                        if (W == 4)
+                            reinterpret_cast<unsigned*>(out)[e0 + c] = d[c];
+                        else
+                            reinterpret_cast<unsigned short*>(out)[e0 + c] = static_cast<unsigned short>(
+                                (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
+                    }
                 }
             }
         }
+        wave_lds_sync();
     }
 }
 
@@ -511,12 +688,26 @@ inline bool ranges_overlap(const void* a, size_t an, const void* b, size_t bn) {
 
 inline zvc_status hip_ok(hipError_t e) { return e == hipSuccess ? ZVC_OK : ZVC_E_HIP; }
 
-zvc_status launch_reset(void* d_ws, size_t slots, hipStream_t stream) {
-    const size_t words = kHeaderBytes / 8 + slots;
+// Zeroes the header and the first state_bytes bytes of scan state.
+zvc_status launch_reset(void* d_ws, size_t state_bytes, hipStream_t stream) {
+    const size_t words = (kHeaderBytes + state_bytes) / 8;
     const unsigned blocks = static_cast<unsigned>(div_up(words, 256) < 1024 ? div_up(words, 256) : 1024);
     hipLaunchKernelGGL(reset_kernel, dim3(blocks), dim3(256), 0, stream,
-                       static_cast<unsigned long long*>(d_ws), kHeaderBytes / 8, slots);
+                       static_cast<unsigned long long*>(d_ws), words);
     return hip_ok(hipGetLastError());
+}
+
+// Where the scan state of a call with `tiles` tiles lives inside the workspace.
+struct ScanState {
+    WsHeader* hdr;
+    unsigned* counts;
+    unsigned long long* prefixes;
+};
+inline ScanState scan_state(void* d_ws, size_t tiles) {
+    unsigned char* base = static_cast<unsigned char*>(d_ws);
+    return ScanState{reinterpret_cast<WsHeader*>(base),
+                     reinterpret_cast<unsigned*>(base + kHeaderBytes),
+                     reinterpret_cast<unsigned long long*>(base + kHeaderBytes + counts_bytes(tiles))};
 }
 
 zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
@@ -524,6 +715,73 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
     if (!aligned_to(d_ws, 256)) return ZVC_E_ALIGN;
     if (ws < zvc_workspace_bytes(n, w)) return ZVC_E_WORKSPACE;
     return ZVC_OK;
+}
+
+// Polls a waiting tile makes before it computes a missing predecessor's count
+// itself.  A poll is one memory round trip (about a microsecond).
+constexpr unsigned kDefaultPatience = 2000;
+std::atomic<unsigned> g_patience{kDefaultPatience};
+
+// Tile size: 32 KB tiles halve the number of tiles the scan has to chain and
+// are used once the tensor is large enough to still give every CU several
+// tiles; smaller tensors keep 16 KB tiles.
+#ifndef ZVC_FORCE_LOADS
+#define ZVC_FORCE_LOADS 0
+#endif
+constexpr size_t kLargeTensorBytes = size_t{32} << 20;
+
+inline int choose_loads(size_t n, int w, bool aligned) {
+    if (!aligned) return kMinLoads;
+    if (ZVC_FORCE_LOADS != 0) return ZVC_FORCE_LOADS;
+    return n * static_cast<size_t>(w) >= kLargeTensorBytes ? 8 : 4;
+}
+
+template <int W, int LOADS, bool ALIGNED>
+void launch_compress_as(dim3 grid, hipStream_t stream, const unsigned char* in, size_t n,
+                        unsigned* masks, unsigned char* values, ScanState st,
+                        unsigned long long* d_bytes, unsigned tiles, size_t groups) {
+    hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream, in, n,
+                       masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles, groups,
+                       g_patience.load(std::memory_order_relaxed));
+}
+
+template <int W, int LOADS, bool ALIGNED>
+void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
+                          const unsigned char* values, unsigned long long avail, size_t n,
+                          unsigned char* out, ScanState st, size_t groups) {
+    hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
+                       masks, values, avail, n, out, st.hdr, st.counts, st.prefixes, groups,
+                       g_patience.load(std::memory_order_relaxed));
+}
+
+// Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
+// use the smallest tile.
+template <typename... Args>
+void launch_compress(int w, int loads, bool aligned, Args... args) {
+    if (!aligned) {
+        if (w == 4) launch_compress_as<4, kMinLoads, false>(args...);
+        else launch_compress_as<2, kMinLoads, false>(args...);
+    } else if (loads == 8) {
+        if (w == 4) launch_compress_as<4, 8, true>(args...);
+        else launch_compress_as<2, 8, true>(args...);
+    } else {
+        if (w == 4) launch_compress_as<4, 4, true>(args...);
+        else launch_compress_as<2, 4, true>(args...);
+    }
+}
+
+template <typename... Args>
+void launch_decompress(int w, int loads, bool aligned, Args... args) {
+    if (!aligned) {
+        if (w == 4) launch_decompress_as<4, kMinLoads, false>(args...);
+        else launch_decompress_as<2, kMinLoads, false>(args...);
+    } else if (loads == 8) {
+        if (w == 4) launch_decompress_as<4, 8, true>(args...);
+        else launch_decompress_as<2, 8, true>(args...);
+    } else {
+        if (w == 4) launch_decompress_as<4, 4, true>(args...);
+        else launch_decompress_as<2, 4, true>(args...);
+    }
 }
 
 }  // namespace
@@ -554,7 +812,7 @@ size_t zvc_max_compressed_bytes(size_t n, int w) {
 
 size_t zvc_workspace_bytes(size_t n, int w) {
     if (w != 2 && w != 4) return 0;
-    return kHeaderBytes + 8 * tiles_for(n, w);
+    return kHeaderBytes + scan_state_bytes(tiles_for(n, w, kMinLoads));
 }
 
 zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w) {
@@ -577,7 +835,17 @@ zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream) {
     if (d_ws == nullptr) return ZVC_E_ARG;
     if (!aligned_to(d_ws, 256)) return ZVC_E_ALIGN;
     if (ws < kHeaderBytes) return ZVC_E_WORKSPACE;
-    return launch_reset(d_ws, (ws - kHeaderBytes) / 8, stream);
+    return launch_reset(d_ws, (ws - kHeaderBytes) / 8 * 8, stream);
+}
+
+void zvc_set_lookback_patience(unsigned polls) {
+    g_patience.store(polls, std::memory_order_relaxed);
+}
+
+zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count) {
+    if (d_ws == nullptr || h_count == nullptr) return ZVC_E_ARG;
+    const WsHeader* hdr = static_cast<const WsHeader*>(d_ws);
+    return hip_ok(hipMemcpy(h_count, &hdr->helped, 8, hipMemcpyDeviceToHost));
 }
 
 zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_bytes, void* d_ws,
@@ -596,8 +864,9 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(n * static_cast<size_t>(w), 16);
+    // one same-address atomic per block: keep the block count low
     size_t blocks = div_up(chunks, static_cast<size_t>(kThreads) * 8);
-    if (blocks > 4096) blocks = 4096;
+    if (blocks > 1024) blocks = 1024;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const bool al = aligned_to(d_in, 16);
     if (w == 4) {
@@ -626,26 +895,17 @@ zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t o
         hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out_bytes, 0ull);
         return hip_ok(hipGetLastError());
     }
-    const size_t tiles = tiles_for(n, w);
+    const bool al = aligned_to(d_in, 16);
+    const int loads = choose_loads(n, w, al);
+    const size_t tiles = tiles_for(n, w, loads);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
-    if (zvc_status st = launch_reset(d_ws, tiles, stream)) return st;
-    WsHeader* hdr = static_cast<WsHeader*>(d_ws);
-    unsigned long long* states =
-        reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(d_ws) + kHeaderBytes);
+    if (zvc_status st = launch_reset(d_ws, scan_state_bytes(tiles), stream)) return st;
     const size_t groups = div_up(n, 32);
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
     unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    const dim3 grid(static_cast<unsigned>(tiles)), block(kThreads);
-    const unsigned nt = static_cast<unsigned>(tiles);
-    const bool al = aligned_to(d_in, 16);
-    if (w == 4) {
-        if (al) hipLaunchKernelGGL((compress_kernel<4, true>), grid, block, 0, stream, in, n, masks, values, hdr, states, out_bytes, nt, groups);
-        else hipLaunchKernelGGL((compress_kernel<4, false>), grid, block, 0, stream, in, n, masks, values, hdr, states, out_bytes, nt, groups);
-    } else {
-        if (al) hipLaunchKernelGGL((compress_kernel<2, true>), grid, block, 0, stream, in, n, masks, values, hdr, states, out_bytes, nt, groups);
-        else hipLaunchKernelGGL((compress_kernel<2, false>), grid, block, 0, stream, in, n, masks, values, hdr, states, out_bytes, nt, groups);
-    }
+    launch_compress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, in, n, masks, values,
+                    scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups);
     return hip_ok(hipGetLastError());
 }
 
@@ -658,26 +918,17 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     if (ranges_overlap(d_comp, comp_bytes, d_out, n * static_cast<size_t>(w))) return ZVC_E_ARG;
     if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
     if (n == 0) return ZVC_OK;
-    const size_t tiles = tiles_for(n, w);
+    const bool al = aligned_to(d_out, 16);
+    const int loads = choose_loads(n, w, al);
+    const size_t tiles = tiles_for(n, w, loads);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
-    if (zvc_status st = launch_reset(d_ws, tiles, stream)) return st;
-    WsHeader* hdr = static_cast<WsHeader*>(d_ws);
-    unsigned long long* states =
-        reinterpret_cast<unsigned long long*>(static_cast<unsigned char*>(d_ws) + kHeaderBytes);
+    if (zvc_status st = launch_reset(d_ws, scan_state_bytes(tiles), stream)) return st;
     const size_t groups = div_up(n, 32);
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
-    unsigned char* out = static_cast<unsigned char*>(d_out);
-    const dim3 grid(static_cast<unsigned>(tiles)), block(kThreads);
-    const bool al = aligned_to(d_out, 16);
-    if (w == 4) {
-        if (al) hipLaunchKernelGGL((decompress_kernel<4, true>), grid, block, 0, stream, masks, values, avail, n, out, hdr, states, groups);
-        else hipLaunchKernelGGL((decompress_kernel<4, false>), grid, block, 0, stream, masks, values, avail, n, out, hdr, states, groups);
-    } else {
-        if (al) hipLaunchKernelGGL((decompress_kernel<2, true>), grid, block, 0, stream, masks, values, avail, n, out, hdr, states, groups);
-        else hipLaunchKernelGGL((decompress_kernel<2, false>), grid, block, 0, stream, masks, values, avail, n, out, hdr, states, groups);
-    }
+    launch_decompress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values,
+                      avail, n, static_cast<unsigned char*>(d_out), scan_state(d_ws, tiles), groups);
     return hip_ok(hipGetLastError());
 }
 

@@ -13,7 +13,8 @@ from typing import Optional, Tuple
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIBRARY = os.path.join(_PKG, "libzvc.so")
+# ZVC_LIBRARY selects another build of the same library (tuning experiments)
+LIBRARY = os.environ.get("ZVC_LIBRARY") or os.path.join(_PKG, "libzvc.so")
 
 STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_WORKSPACE",
                 "ZVC_E_ALIGN", "ZVC_E_HIP", "ZVC_E_CORRUPT")
@@ -24,7 +25,7 @@ STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_W
 EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
-           "zvc_prefetch")
+           "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count")
 
 _lib = None
 
@@ -68,6 +69,10 @@ def load() -> ctypes.CDLL:
     lib.zvc_offload.argtypes = [vp, sz, ci, vp, sz, vp, sz, vp, vp, sz, vp, vp]
     lib.zvc_prefetch.restype = ci
     lib.zvc_prefetch.argtypes = [vp, u64, sz, ci, vp, sz, vp, vp, sz, vp, vp]
+    lib.zvc_set_lookback_patience.restype = None
+    lib.zvc_set_lookback_patience.argtypes = [ctypes.c_uint]
+    lib.zvc_workspace_self_help_count.restype = ci
+    lib.zvc_workspace_self_help_count.argtypes = [vp, vp]
     _lib = lib
     return lib
 
@@ -108,6 +113,17 @@ def zvc_check_stream(h_comp: torch.Tensor, nbytes: int, n: int, w: int) -> int:
     Returns the status code (ZVC_OK or an error), it does not raise."""
     assert h_comp.device.type == "cpu" and h_comp.is_contiguous()
     return int(load().zvc_check_stream(h_comp.data_ptr(), nbytes, n, w))
+
+
+def zvc_set_lookback_patience(polls: int) -> None:
+    load().zvc_set_lookback_patience(int(polls))
+
+
+def zvc_workspace_self_help_count(ws: torch.Tensor) -> int:
+    count = ctypes.c_uint64(0)
+    _check(load().zvc_workspace_self_help_count(ws.data_ptr(), ctypes.byref(count)),
+           "zvc_workspace_self_help_count")
+    return int(count.value)
 
 
 # ---- buffers -------------------------------------------------------------------
