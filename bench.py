@@ -108,6 +108,9 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--counter-pass", action="store_true",
+                    help="for rocprofv3 --pmc runs: a few rounds of [plain device copy of the "
+                         "tensor, zvc_compress, zvc_decompress] and nothing else")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the hot path is single-GPU; "
@@ -143,6 +146,17 @@ def main() -> int:
     def step():
         compress()
         decompress()
+
+    if args.counter_pass:
+        # the plain copy (n*w bytes read, n*w bytes written) calibrates the counters
+        for _ in range(max(1, args.steps)):
+            out.copy_(x)
+            compress()
+            decompress()
+        torch.cuda.synchronize()
+        print(json.dumps({"counter_pass": True, "workload": args.workload,
+                          "uncompressed_bytes": n * w, "compressed_bytes": nbytes}))
+        return 0
 
     for _ in range(args.warmup):
         step()
