@@ -58,7 +58,10 @@ struct Geometry {
     static constexpr int kMasksPerThread = kTileGroups > kThreads ? kTileGroups / kThreads : 1;
     // per-wave LDS staging buffer: kStageLoads wave-loads plus alignment slack
     static constexpr int kStageSteps = LOADS / kStageLoads;
-    static constexpr int kWaveStageBytes = kStageLoads * kWaveSize * 16 + 16;
+    // (16 bytes so the slice can mirror the destination's alignment) and one
+    // 4-byte dump word per lane for elements that are not kept
+    static constexpr int kDumpOffset = kStageLoads * kWaveSize * 16 + 16;
+    static constexpr int kWaveStageBytes = kDumpOffset + 4 * kWaveSize;
     static_assert(LOADS % kStageLoads == 0, "tile is staged in whole steps");
 };
 
@@ -104,16 +107,39 @@ __device__ inline void store32(unsigned* p, unsigned v) {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Number of set bits of `ballot` in lanes below the calling lane.
-__device__ inline unsigned lanes_below(unsigned long long ballot) {
+// acc + number of set bits of `ballot` in lanes below the calling lane.
+__device__ inline unsigned lanes_below(unsigned long long ballot, unsigned acc) {
     return __builtin_amdgcn_mbcnt_hi(static_cast<unsigned>(ballot >> 32),
-                                     __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(ballot), 0u));
+                                     __builtin_amdgcn_mbcnt_lo(static_cast<unsigned>(ballot), acc));
 }
 
 __device__ inline unsigned long long wave_sum(unsigned long long v) {
 #pragma unroll
     for (int off = 1; off < kWaveSize; off <<= 1) v += __shfl_xor(v, off);
     return v;
+}
+
+// A value that is the same in every lane, moved to scalar registers so that
+// address arithmetic built on it stays scalar.
+__device__ inline unsigned uniform(unsigned v) {
+    return static_cast<unsigned>(__builtin_amdgcn_readfirstlane(static_cast<int>(v)));
+}
+__device__ inline unsigned long long uniform(unsigned long long v) {
+    return (static_cast<unsigned long long>(uniform(static_cast<unsigned>(v >> 32))) << 32) |
+           uniform(static_cast<unsigned>(v));
+}
+
+// OR over each aligned group of LANES lanes (8 or 4), result in every lane of
+// the group.  DPP: swap within pairs, swap pairs within quads, then (8 lanes)
+// mirror the half-row; after the quad steps all lanes of a quad agree, so the
+// mirror pairs the two quads.
+template <int LANES>
+__device__ inline unsigned group_or(unsigned m) {
+    m |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(m), 0xB1, 0xF, 0xF, true));
+    m |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(m), 0x4E, 0xF, 0xF, true));
+    if (LANES == 8)
+        m |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(m), 0x141, 0xF, 0xF, true));
+    return m;
 }
 
 // LDS written by some lanes of a wave is read by other lanes of the same wave:
@@ -171,55 +197,72 @@ __device__ inline unsigned element_of(const uint4& v, int c) {
     return (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
 }
 
+// Is element c of the lane's 16 bytes non-zero as an integer?
+template <int W>
+__device__ inline bool element_nonzero(const uint4& v, int c) {
+    const unsigned d[4] = {v.x, v.y, v.z, v.w};
+    if (W == 4) return d[c] != 0u;
+    return (c & 1) ? (d[c >> 1] > 0xFFFFu) : ((d[c >> 1] & 0xFFFFu) != 0u);
+}
+
 // Copies LDS bytes [shift, end) to global memory at gbase + same offsets, where
-// gbase is 16-byte aligned: whole 16-byte chunks as one store, the ragged first
-// and last chunk element by element.  Called by one wave.
+// gbase is 16-byte aligned and wave-uniform: whole 16-byte chunks as one store,
+// the ragged head and tail (under 16 bytes each) element by element.
 template <int W>
 __device__ inline void wave_copy_out(unsigned char* gbase, const unsigned char* stage,
                                      unsigned shift, unsigned end, int lane) {
-    const unsigned chunks = (end + 15u) / 16u;
-    for (unsigned q = lane; q < chunks; q += kWaveSize) {
-        const unsigned lo = q * 16u, hi = lo + 16u;
-        if (lo >= shift && hi <= end) {
-            *reinterpret_cast<uint4*>(gbase + lo) = *reinterpret_cast<const uint4*>(stage + lo);
-        } else {
-            const unsigned a = lo > shift ? lo : shift;
-            const unsigned b = hi < end ? hi : end;
-            for (unsigned o = a; o < b; o += W) {
-                if (W == 4)
-                    *reinterpret_cast<unsigned*>(gbase + o) =
-                        *reinterpret_cast<const unsigned*>(stage + o);
-                else
-                    *reinterpret_cast<unsigned short*>(gbase + o) =
-                        *reinterpret_cast<const unsigned short*>(stage + o);
-            }
-        }
+    const unsigned first_full = (shift + 15u) >> 4;   // chunk indices
+    const unsigned last_full = end >> 4;
+    for (unsigned q = first_full + lane; q < last_full; q += kWaveSize)
+        *reinterpret_cast<uint4*>(gbase + q * 16u) = *reinterpret_cast<const uint4*>(stage + q * 16u);
+    const unsigned head_end = min(end, first_full * 16u);
+    const unsigned tail_begin = max(max(shift, last_full * 16u), head_end);
+    const unsigned oh = shift + W * lane;
+    const unsigned ot = tail_begin + W * lane;
+    if (W == 4) {
+        if (oh < head_end)
+            *reinterpret_cast<unsigned*>(gbase + oh) = *reinterpret_cast<const unsigned*>(stage + oh);
+        if (ot < end)
+            *reinterpret_cast<unsigned*>(gbase + ot) = *reinterpret_cast<const unsigned*>(stage + ot);
+    } else {
+        if (oh < head_end)
+            *reinterpret_cast<unsigned short*>(gbase + oh) =
+                *reinterpret_cast<const unsigned short*>(stage + oh);
+        if (ot < end)
+            *reinterpret_cast<unsigned short*>(gbase + ot) =
+                *reinterpret_cast<const unsigned short*>(stage + ot);
     }
 }
 
 // The mirror: global bytes [shift, end) at gbase into LDS at the same offsets;
-// bytes at or past end_valid are not read and become zero.  Called by one wave.
+// bytes at or past end_valid (<= end) are not read and become zero.
 template <int W>
 __device__ inline void wave_copy_in(unsigned char* stage, const unsigned char* gbase,
                                     unsigned shift, unsigned end, unsigned end_valid, int lane) {
-    const unsigned chunks = (end + 15u) / 16u;
-    for (unsigned q = lane; q < chunks; q += kWaveSize) {
-        const unsigned lo = q * 16u, hi = lo + 16u;
-        if (lo >= shift && hi <= end_valid) {
-            *reinterpret_cast<uint4*>(stage + lo) = *reinterpret_cast<const uint4*>(gbase + lo);
-        } else {
-            const unsigned a = lo > shift ? lo : shift;
-            const unsigned b = hi < end ? hi : end;
-            for (unsigned o = a; o < b; o += W) {
-                if (W == 4)
-                    *reinterpret_cast<unsigned*>(stage + o) =
-                        o < end_valid ? *reinterpret_cast<const unsigned*>(gbase + o) : 0u;
-                else
-                    *reinterpret_cast<unsigned short*>(stage + o) =
-                        o < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + o)
-                                      : static_cast<unsigned short>(0);
-            }
-        }
+    const unsigned first_full = (shift + 15u) >> 4;
+    const unsigned last_full = end_valid >> 4;
+    for (unsigned q = first_full + lane; q < last_full; q += kWaveSize)
+        *reinterpret_cast<uint4*>(stage + q * 16u) = *reinterpret_cast<const uint4*>(gbase + q * 16u);
+    const unsigned head_end = min(end, first_full * 16u);
+    const unsigned tail_begin = max(max(shift, last_full * 16u), head_end);
+    const unsigned oh = shift + W * lane;
+    if (W == 4) {
+        if (oh < head_end)
+            *reinterpret_cast<unsigned*>(stage + oh) =
+                oh < end_valid ? *reinterpret_cast<const unsigned*>(gbase + oh) : 0u;
+        // under 16 bytes unless the stream is cut short (then the rest is zero fill)
+        for (unsigned o = tail_begin + W * lane; o < end; o += W * kWaveSize)
+            *reinterpret_cast<unsigned*>(stage + o) =
+                o < end_valid ? *reinterpret_cast<const unsigned*>(gbase + o) : 0u;
+    } else {
+        if (oh < head_end)
+            *reinterpret_cast<unsigned short*>(stage + oh) =
+                oh < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + oh)
+                               : static_cast<unsigned short>(0);
+        for (unsigned o = tail_begin + W * lane; o < end; o += W * kWaveSize)
+            *reinterpret_cast<unsigned short*>(stage + o) =
+                o < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + o)
+                              : static_cast<unsigned short>(0);
     }
 }
 
@@ -384,7 +427,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
-    constexpr int kBitWords = (LOADS * E + 31) / 32;
 
     __shared__ __align__(16) unsigned char s_stage[kWaves][G::kWaveStageBytes];
     __shared__ unsigned s_wave_total[kWaves];
@@ -392,45 +434,51 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
-    const int wave = tid / kWaveSize;
+    const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
 
-    // ---- load, zero test, in-wave ranks, masks
+    // ---- load: LOADS x 16 bytes per lane, 1 KB per wave instruction.  A tile
+    //      that lies wholly inside an aligned tensor needs no bounds checks.
     uint4 data[LOADS];
+    if (ALIGNED && tile_elem0 + G::kTileElems <= n) {
+        const uint4* wave_base = reinterpret_cast<const uint4*>(in + tile_elem0 * W) +
+                                 static_cast<size_t>(wave) * LOADS * kWaveSize;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        const size_t e0 =
-            tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
-        data[j] = load_chunk<W, ALIGNED>(in, e0, n);
+        for (int j = 0; j < LOADS; ++j) data[j] = wave_base[j * kWaveSize + lane];
+    } else {
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const size_t e0 =
+                tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
+            data[j] = load_chunk<W, ALIGNED>(in, e0, n);
+        }
     }
-    unsigned bit_words[kBitWords];   // the lane's presence bits, E per load
+
+    // ---- zero test, in-wave ranks (section 5.2: prefix sum over the mask bits), masks
     unsigned below16[LOADS / 2];     // kept elements of lower lanes in the same load, 16 bits each
     unsigned run[LOADS + 1];         // wave-uniform: kept elements of the wave's earlier loads
     unsigned my_mask[G::kMaskRegs];
 #pragma unroll
-    for (int k = 0; k < kBitWords; ++k) bit_words[k] = 0;
-#pragma unroll
     for (int k = 0; k < LOADS / 2; ++k) below16[k] = 0;
     run[0] = 0;
     const int lane_in_group = lane % LPG;
+    const unsigned field_shift = static_cast<unsigned>(E * lane_in_group);
 #pragma unroll
     for (int j = 0; j < LOADS; ++j) {
-        const unsigned bits = presence_bits<W>(data[j]);
-        unsigned below = 0, load_total = 0;
+        unsigned bits = 0, below = 0, load_total = 0;
 #pragma unroll
         for (int c = 0; c < E; ++c) {
-            const unsigned long long b = __ballot((bits >> c) & 1u);
-            below += lanes_below(b);
+            const bool nz = element_nonzero<W>(data[j], c);
+            const unsigned long long b = __ballot(nz);
+            below = lanes_below(b, below);
             load_total += static_cast<unsigned>(__popcll(b));
+            bits |= (nz ? 1u : 0u) << c;
         }
-        bit_words[(j * E) / 32] |= bits << ((j * E) % 32);
         below16[j / 2] |= below << (16 * (j % 2));
         run[j + 1] = run[j] + load_total;
         // the group's mask: OR of the lanes' bit fields, each at its position
-        unsigned m = bits << (E * lane_in_group);
-#pragma unroll
-        for (int off = 1; off < LPG; off <<= 1) m |= __shfl_xor(m, off);
+        const unsigned m = group_or<LPG>(bits << field_shift);
         if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
     }
 #pragma unroll
@@ -450,7 +498,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     unsigned wave_offset = 0, tile_total = 0;
 #pragma unroll
     for (int v = 0; v < kWaves; ++v) {
-        const unsigned t = s_wave_total[v];
+        const unsigned t = uniform(s_wave_total[v]);
         if (v < wave) wave_offset += t;
         tile_total += t;
     }
@@ -463,36 +511,37 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
         if (lane == 0) s_prefix = ex;
     }
     __syncthreads();
-    const unsigned long long exclusive = s_prefix;
+    const unsigned long long exclusive = uniform(s_prefix);
 
     // ---- compaction (section 5.2: shift non-zeros to their packed slots).
-    //      Each wave stages kStageLoads loads at a time in its own LDS slice at
-    //      the elements' packed order, then copies the run out.  LDS byte p of
-    //      the slice corresponds to global byte (dst - shift) + p, so 16-byte
-    //      chunks are aligned on both sides.
+    //      Each wave stages kStageLoads loads at a time in its own LDS slice in
+    //      packed order, then copies the run out.  LDS byte p of the slice
+    //      corresponds to global byte (dst - shift) + p, so 16-byte chunks are
+    //      aligned on both sides.  Elements that are not kept go to a per-lane
+    //      dump word: every lane issues every LDS write, no branches.
     unsigned char* stage = s_stage[wave];
+    const unsigned dump = G::kDumpOffset + 4u * lane;
 #pragma unroll
     for (int h = 0; h < G::kStageSteps; ++h) {
         const unsigned first_rank = run[h * kStageLoads];
         const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
-        unsigned char* dst = values + (exclusive + wave_offset + first_rank) * W;
+        unsigned char* dst = values + (exclusive + wave_offset + first_rank) * W;  // wave-uniform
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
 #pragma unroll
         for (int jj = 0; jj < kStageLoads; ++jj) {
             const int j = h * kStageLoads + jj;
-            unsigned r = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
-            const unsigned bits = bit_words[(j * E) / 32] >> ((j * E) % 32);
+            unsigned a = shift + W * ((run[j] - first_rank) +
+                                      ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu));
 #pragma unroll
             for (int c = 0; c < E; ++c) {
-                if ((bits >> c) & 1u) {
-                    const unsigned v = element_of<W>(data[j], c);
-                    if (W == 4)
-                        *reinterpret_cast<unsigned*>(stage + shift + r * 4u) = v;
-                    else
-                        *reinterpret_cast<unsigned short*>(stage + shift + r * 2u) =
-                            static_cast<unsigned short>(v);
-                    ++r;
-                }
+                const bool nz = element_nonzero<W>(data[j], c);
+                const unsigned at = nz ? a : dump;
+                const unsigned v = element_of<W>(data[j], c);
+                if (W == 4)
+                    *reinterpret_cast<unsigned*>(stage + at) = v;
+                else
+                    *reinterpret_cast<unsigned short*>(stage + at) = static_cast<unsigned short>(v);
+                a += nz ? W : 0;
             }
         }
         wave_lds_sync();
@@ -526,7 +575,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
-    const int wave = tid / kWaveSize;
+    const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
 
@@ -556,7 +605,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     unsigned wave_offset = 0, tile_total = 0;
 #pragma unroll
     for (int v = 0; v < kWaves; ++v) {
-        const unsigned t = s_wave_total[v];
+        const unsigned t = uniform(s_wave_total[v]);
         if (v < wave) wave_offset += t;
         tile_total += t;
     }
@@ -581,19 +630,21 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
         if (lane == 0) s_prefix = ex;
     }
     __syncthreads();
-    const unsigned long long exclusive = s_prefix;
+    const unsigned long long exclusive = uniform(s_prefix);
+    const bool full_tile = ALIGNED && tile_elem0 + G::kTileElems <= n;
 
     // ---- expand (section 5.2: payload words or zeros muxed into place).  Each
     //      wave stages the stored elements of kStageLoads loads' worth of output
-    //      in its LDS slice, then every lane rebuilds 16 bytes per load.
+    //      in its LDS slice, then every lane rebuilds 16 bytes per load.  Slots
+    //      whose bit is clear read a valid dummy address and select zero.
     unsigned char* stage = s_stage[wave];
 #pragma unroll
     for (int h = 0; h < G::kStageSteps; ++h) {
         const int g0 = (wave * LOADS + h * kStageLoads) * G::kGroupsPerLoad;
-        const unsigned first_rank = s_group_offset[g0];
-        const unsigned step_total = s_group_offset[g0 + kStepGroups] - first_rank;
+        const unsigned first_rank = uniform(s_group_offset[g0]);
+        const unsigned step_total = uniform(s_group_offset[g0 + kStepGroups]) - first_rank;
         const unsigned long long step_begin = exclusive + first_rank;
-        const unsigned char* src = values + step_begin * W;
+        const unsigned char* src = values + step_begin * W;  // wave-uniform
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
         unsigned long long readable = values_avail > step_begin ? values_avail - step_begin : 0ull;
         if (readable > step_total) readable = step_total;
@@ -604,27 +655,28 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
         for (int jj = 0; jj < kStageLoads; ++jj) {
             const int seg = wave * LOADS + h * kStageLoads + jj;
             const size_t e0 = tile_elem0 + (static_cast<size_t>(seg) * kWaveSize + lane) * E;
-            if (e0 >= n) continue;
             const int gi = seg * G::kGroupsPerLoad + lane / LPG;
             const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
             const unsigned gm = s_mask[gi];
-            unsigned r = s_group_offset[gi] - first_rank + __popc(gm & ((1u << bit0) - 1u));
+            unsigned a = shift + W * (s_group_offset[gi] - first_rank + __popc(gm & ((1u << bit0) - 1u)));
             const unsigned field = gm >> bit0;
             unsigned d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int c = 0; c < E; ++c) {
-                if ((field >> c) & 1u) {
-                    if (W == 4) {
-                        d[c] = *reinterpret_cast<const unsigned*>(stage + shift + r * 4u);
-                    } else {
-                        const unsigned v =
-                            *reinterpret_cast<const unsigned short*>(stage + shift + r * 2u);
-                        d[c >> 1] |= v << (16 * (c & 1));
-                    }
-                    ++r;
+                const bool set = (field >> c) & 1u;
+                const unsigned at = set ? a : shift;
+                if (W == 4) {
+                    const unsigned v = *reinterpret_cast<const unsigned*>(stage + at);
+                    d[c] = set ? v : 0u;
+                } else {
+                    const unsigned v = *reinterpret_cast<const unsigned short*>(stage + at);
+                    d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
                 }
+                a += set ? W : 0;
             }
-            if (ALIGNED && e0 + E <= n) {
+            if (full_tile) {
+                *reinterpret_cast<uint4*>(out + e0 * W) = make_uint4(d[0], d[1], d[2], d[3]);
+            } else if (ALIGNED && e0 + E <= n) {
                 *reinterpret_cast<uint4*>(out + e0 * W) = make_uint4(d[0], d[1], d[2], d[3]);
             } else {
 #pragma unroll
@@ -722,18 +774,20 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
 constexpr unsigned kDefaultPatience = 2000;
 std::atomic<unsigned> g_patience{kDefaultPatience};
 
-// Tile size: 32 KB tiles halve the number of tiles the scan has to chain and
-// are used once the tensor is large enough to still give every CU several
-// tiles; smaller tensors keep 16 KB tiles.
+// Tile size.  Each tile costs a fixed few nanoseconds of chip-wide time
+// (workgroup launch plus the scan's state traffic), so large tensors use 64 KB
+// tiles; smaller tensors use smaller tiles so that every CU still gets several.
 #ifndef ZVC_FORCE_LOADS
 #define ZVC_FORCE_LOADS 0
 #endif
-constexpr size_t kLargeTensorBytes = size_t{32} << 20;
+constexpr size_t kLargeTensorBytes = size_t{96} << 20;
+constexpr size_t kMediumTensorBytes = size_t{24} << 20;
 
 inline int choose_loads(size_t n, int w, bool aligned) {
     if (!aligned) return kMinLoads;
     if (ZVC_FORCE_LOADS != 0) return ZVC_FORCE_LOADS;
-    return n * static_cast<size_t>(w) >= kLargeTensorBytes ? 8 : 4;
+    const size_t bytes = n * static_cast<size_t>(w);
+    return bytes >= kLargeTensorBytes ? 16 : bytes >= kMediumTensorBytes ? 8 : 4;
 }
 
 template <int W, int LOADS, bool ALIGNED>
@@ -761,6 +815,9 @@ void launch_compress(int w, int loads, bool aligned, Args... args) {
     if (!aligned) {
         if (w == 4) launch_compress_as<4, kMinLoads, false>(args...);
         else launch_compress_as<2, kMinLoads, false>(args...);
+    } else if (loads == 16) {
+        if (w == 4) launch_compress_as<4, 16, true>(args...);
+        else launch_compress_as<2, 16, true>(args...);
     } else if (loads == 8) {
         if (w == 4) launch_compress_as<4, 8, true>(args...);
         else launch_compress_as<2, 8, true>(args...);
@@ -775,6 +832,9 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
     if (!aligned) {
         if (w == 4) launch_decompress_as<4, kMinLoads, false>(args...);
         else launch_decompress_as<2, kMinLoads, false>(args...);
+    } else if (loads == 16) {
+        if (w == 4) launch_decompress_as<4, 16, true>(args...);
+        else launch_decompress_as<2, 16, true>(args...);
     } else if (loads == 8) {
         if (w == 4) launch_decompress_as<4, 8, true>(args...);
         else launch_decompress_as<2, 8, true>(args...);

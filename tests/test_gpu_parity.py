@@ -63,6 +63,16 @@ def test_unaligned_tensor_pointers(oracle, w, offset_elems):
         assert int(out_base[offset_elems + n:].abs().sum()) == 0
 
 
+@pytest.mark.parametrize("w,n", [(4, 26000003), (2, 52000007)])
+def test_largest_tile_kernels(oracle, w, n):
+    """Tensors past 96 MB use the 64 KB tile kernels; ragged size, two densities."""
+    ws = zvc.new_workspace(n, w, DEV)
+    for k, density in enumerate((0.08, 0.6)):
+        x = random_tensor(n, w, density, seed=n + k)
+        assert_parity(x, oracle, "64 KB tiles d=%.2f" % density, ws)
+        del x
+
+
 def test_compressed_buffer_at_4_byte_alignment(oracle):
     """The compressed buffer only needs 4-byte alignment."""
     n, w = 50000, 4
