@@ -95,6 +95,8 @@ inline size_t prefixes_bytes(size_t tiles) { return 8 * div_up(tiles, kBlockTile
 inline size_t scan_state_bytes(size_t tiles) {
     return counts_bytes(tiles) + div_up(prefixes_bytes(tiles), 256) * 256;
 }
+// the decoder's per-tile offsets (64-bit each) follow the scan state of the largest call
+inline size_t tile_prefix_bytes(size_t tiles) { return div_up(8 * tiles, 256) * 256; }
 
 // ------------------------------------------------------------ device helpers
 __device__ inline unsigned long long load64(const unsigned long long* p) {
@@ -554,13 +556,90 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
         *d_bytes = 4ull * num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
 }
 
+// Decoder pre-pass (section 5.2: the popcount of a mask span is the number of
+// stored words the span consumes).  The offsets of the decoder's tiles depend
+// on the masks alone, which are 1/32 (fp32) or 1/16 (16-bit) of the tensor, so
+// they are computed ahead of the decoder, which then has no dependency between
+// workgroups at all.  One workgroup takes a chunk of kChunkMasks consecutive
+// masks (16 per thread), i.e. kChunkMasks / tile_masks whole decoder tiles;
+// chunks are chained by the device-wide scan; the first thread of every tile
+// writes tile_prefix[tile] = stored elements before that tile.
+constexpr int kChunkMasksPerThread = 16;
+constexpr int kChunkMasks = kThreads * kChunkMasksPerThread;  // 4096 masks = 131072 elements
+
+__global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
+    const unsigned* __restrict__ masks, size_t num_groups, unsigned tail, unsigned tile_masks,
+    unsigned num_tiles, unsigned long long* __restrict__ tile_prefix, WsHeader* hdr,
+    unsigned* counts, unsigned long long* prefixes, unsigned patience) {
+    __shared__ unsigned s_wave_total[kWaves];
+    __shared__ unsigned long long s_prefix;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid / kWaveSize;
+    const unsigned chunk = blockIdx.x;
+    const size_t g0 = static_cast<size_t>(chunk) * kChunkMasks +
+                      static_cast<size_t>(tid) * kChunkMasksPerThread;
+
+    unsigned cnt = 0;
+    if (g0 + kChunkMasksPerThread <= num_groups && !(g0 + kChunkMasksPerThread == num_groups && tail != 0)) {
+        const uint4* p = reinterpret_cast<const uint4*>(masks + g0);  // masks are 4-byte aligned only
+        if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+#pragma unroll
+            for (int k = 0; k < kChunkMasksPerThread / 4; ++k) {
+                const uint4 v = p[k];
+                cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < kChunkMasksPerThread; ++k) cnt += __popc(masks[g0 + k]);
+        }
+    } else {
+        for (int k = 0; k < kChunkMasksPerThread; ++k) {
+            const size_t g = g0 + k;
+            if (g < num_groups) {
+                unsigned m = masks[g];
+                if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;  // bits past n never count
+                cnt += __popc(m);
+            }
+        }
+    }
+    unsigned incl = cnt;
+#pragma unroll
+    for (int off = 1; off < kWaveSize; off <<= 1) {
+        const unsigned t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    if (lane == kWaveSize - 1) s_wave_total[wave] = incl;
+    __syncthreads();
+    unsigned wave_offset = 0, chunk_total = 0;
+#pragma unroll
+    for (int v = 0; v < kWaves; ++v) {
+        const unsigned t = s_wave_total[v];
+        if (v < wave) wave_offset += t;
+        chunk_total += t;
+    }
+    if (wave == 0) {
+        const CountMaskTile count_chunk{masks, num_groups, tail, kChunkMasks};
+        const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, chunk, chunk_total,
+                                                            lane, patience, hdr, count_chunk);
+        if (lane == 0) s_prefix = ex;
+    }
+    __syncthreads();
+    // thread tid starts a decoder tile when its first mask is a multiple of tile_masks
+    const unsigned threads_per_tile = tile_masks / kChunkMasksPerThread;
+    if (tid % threads_per_tile == 0) {
+        const size_t t = g0 / tile_masks;
+        if (t < num_tiles) tile_prefix[t] = s_prefix + wave_offset + incl - cnt;
+    }
+}
+
 // Section 5.2 decoder.  values_avail = number of stored elements that may be
 // read; anything the masks ask for beyond it decodes as zero.
 template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
-    unsigned long long values_avail, size_t n, unsigned char* __restrict__ out, WsHeader* hdr,
-    unsigned* counts, unsigned long long* prefixes, size_t num_groups, unsigned patience) {
+    unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
+    const unsigned long long* __restrict__ tile_prefix, size_t num_groups) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -571,13 +650,14 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     __shared__ unsigned s_mask[G::kTileGroups];
     __shared__ unsigned s_group_offset[G::kTileGroups + 1];  // last entry = tile total
     __shared__ unsigned s_wave_total[kWaves];
-    __shared__ unsigned long long s_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
+    // stored elements in all earlier tiles, from the mask pre-pass
+    const unsigned long long exclusive = uniform(tile_prefix[tile]);
 
     // ---- MPT consecutive masks per thread: popcount, exclusive scan over the tile
     unsigned m[MPT];
@@ -623,14 +703,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
         if (tid == 0) s_group_offset[G::kTileGroups] = tile_total;
     }
 
-    if (wave == 0) {
-        const CountMaskTile count_tile{masks, num_groups, tail, G::kTileGroups};
-        const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, tile, tile_total,
-                                                            lane, patience, hdr, count_tile);
-        if (lane == 0) s_prefix = ex;
-    }
     __syncthreads();
-    const unsigned long long exclusive = uniform(s_prefix);
     const bool full_tile = ALIGNED && tile_elem0 + G::kTileElems <= n;
 
     // ---- expand (section 5.2: payload words or zeros muxed into place).  Each
@@ -802,10 +875,10 @@ void launch_compress_as(dim3 grid, hipStream_t stream, const unsigned char* in, 
 template <int W, int LOADS, bool ALIGNED>
 void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
-                          unsigned char* out, ScanState st, size_t groups) {
+                          unsigned char* out, const unsigned long long* tile_prefix,
+                          size_t groups) {
     hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, st.hdr, st.counts, st.prefixes, groups,
-                       g_patience.load(std::memory_order_relaxed));
+                       masks, values, avail, n, out, tile_prefix, groups);
 }
 
 // Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
@@ -872,7 +945,8 @@ size_t zvc_max_compressed_bytes(size_t n, int w) {
 
 size_t zvc_workspace_bytes(size_t n, int w) {
     if (w != 2 && w != 4) return 0;
-    return kHeaderBytes + scan_state_bytes(tiles_for(n, w, kMinLoads));
+    const size_t tiles = tiles_for(n, w, kMinLoads);
+    return kHeaderBytes + scan_state_bytes(tiles) + tile_prefix_bytes(tiles);
 }
 
 zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w) {
@@ -982,13 +1056,25 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     const int loads = choose_loads(n, w, al);
     const size_t tiles = tiles_for(n, w, loads);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
-    if (zvc_status st = launch_reset(d_ws, scan_state_bytes(tiles), stream)) return st;
     const size_t groups = div_up(n, 32);
+    const size_t chunks = div_up(groups, kChunkMasks);
+    // pre-pass: scan state sized for the chunks; tile offsets after the largest scan state
+    if (zvc_status st = launch_reset(d_ws, scan_state_bytes(chunks), stream)) return st;
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
+    unsigned long long* tile_prefix = reinterpret_cast<unsigned long long*>(
+        static_cast<unsigned char*>(d_ws) + kHeaderBytes +
+        scan_state_bytes(tiles_for(n, w, kMinLoads)));
+    const unsigned tile_masks = static_cast<unsigned>(kThreads * 16 * loads / w / 32);
+    const ScanState st = scan_state(d_ws, chunks);
+    hipLaunchKernelGGL(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), 0,
+                       stream, masks, groups, static_cast<unsigned>(n % 32), tile_masks,
+                       static_cast<unsigned>(tiles), tile_prefix, st.hdr, st.counts, st.prefixes,
+                       g_patience.load(std::memory_order_relaxed));
+    if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
     launch_decompress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values,
-                      avail, n, static_cast<unsigned char*>(d_out), scan_state(d_ws, tiles), groups);
+                      avail, n, static_cast<unsigned char*>(d_out), tile_prefix, groups);
     return hip_ok(hipGetLastError());
 }
 
