@@ -575,18 +575,23 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
 // on the masks alone, which are 1/32 (fp32) or 1/16 (16-bit) of the tensor, so
 // they are computed ahead of the decoder, which then has no dependency between
 // workgroups at all.  One workgroup takes a chunk of kChunkMasks consecutive
-// masks (16 per thread), i.e. kChunkMasks / tile_masks whole decoder tiles;
-// chunks are chained by the device-wide scan; the first thread of every tile
-// writes tile_prefix[tile] = stored elements before that tile.
-constexpr int kChunkMasksPerThread = 16;
-constexpr int kChunkMasks = kThreads * kChunkMasksPerThread;  // 4096 masks = 131072 elements
+// masks (64 per thread), i.e. a whole number of decoder tiles, and writes
+//   tile_local[t]  = stored elements of the chunk before tile t,
+//   chunk_total[c] = stored elements of the chunk.
+// The workgroup that finishes last (one counter increment per chunk; chunks
+// are 2 MB of fp32 output, so these same-address atomics stay far from their
+// ~11 ns serialisation limit) turns the totals into chunk_prefix[c] and puts
+// the counter back to zero, so the workspace needs no reset between calls.
+constexpr int kChunkMasksPerThread = 64;
+constexpr int kChunkMasks = kThreads * kChunkMasksPerThread;  // 16384 masks = 524288 elements
 
 __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     const unsigned* __restrict__ masks, size_t num_groups, unsigned tail, unsigned tile_masks,
-    unsigned num_tiles, unsigned long long* __restrict__ tile_prefix, WsHeader* hdr,
-    unsigned* counts, unsigned long long* prefixes, unsigned patience) {
+    unsigned num_tiles, unsigned num_chunks, unsigned* __restrict__ tile_local,
+    unsigned* chunk_total, unsigned long long* chunk_prefix, WsHeader* hdr) {
     __shared__ unsigned s_wave_total[kWaves];
-    __shared__ unsigned long long s_prefix;
+    __shared__ unsigned long long s_wave_sum[kWaves];
+    __shared__ unsigned s_last;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid / kWaveSize;
@@ -594,18 +599,17 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     const size_t g0 = static_cast<size_t>(chunk) * kChunkMasks +
                       static_cast<size_t>(tid) * kChunkMasksPerThread;
 
+    // ---- the thread's 64 masks (256 bytes).  A decoder tile has at least 128
+    //      masks, so a thread's span never straddles a tile start.
     unsigned cnt = 0;
-    if (g0 + kChunkMasksPerThread <= num_groups && !(g0 + kChunkMasksPerThread == num_groups && tail != 0)) {
-        const uint4* p = reinterpret_cast<const uint4*>(masks + g0);  // masks are 4-byte aligned only
-        if ((reinterpret_cast<uintptr_t>(p) & 15u) == 0) {
+    const bool whole = g0 + kChunkMasksPerThread <= num_groups &&
+                       !(g0 + kChunkMasksPerThread == num_groups && tail != 0);
+    if (whole && (reinterpret_cast<uintptr_t>(masks + g0) & 15u) == 0) {
+        const uint4* p = reinterpret_cast<const uint4*>(masks + g0);
 #pragma unroll
-            for (int k = 0; k < kChunkMasksPerThread / 4; ++k) {
-                const uint4 v = p[k];
-                cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
-            }
-        } else {
-#pragma unroll
-            for (int k = 0; k < kChunkMasksPerThread; ++k) cnt += __popc(masks[g0 + k]);
+        for (int k = 0; k < kChunkMasksPerThread / 4; ++k) {
+            const uint4 v = load16_stream(p + k);
+            cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
         }
     } else {
         for (int k = 0; k < kChunkMasksPerThread; ++k) {
@@ -625,26 +629,55 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     }
     if (lane == kWaveSize - 1) s_wave_total[wave] = incl;
     __syncthreads();
-    unsigned wave_offset = 0, chunk_total = 0;
+    unsigned wave_offset = 0, total = 0;
 #pragma unroll
     for (int v = 0; v < kWaves; ++v) {
         const unsigned t = s_wave_total[v];
         if (v < wave) wave_offset += t;
-        chunk_total += t;
+        total += t;
     }
-    if (wave == 0) {
-        const CountMaskTile count_chunk{masks, num_groups, tail, kChunkMasks};
-        const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, chunk, chunk_total,
-                                                            lane, patience, hdr, count_chunk);
-        if (lane == 0) s_prefix = ex;
-    }
-    __syncthreads();
     // thread tid starts a decoder tile when its first mask is a multiple of tile_masks
     const unsigned threads_per_tile = tile_masks / kChunkMasksPerThread;
     if (tid % threads_per_tile == 0) {
         const size_t t = g0 / tile_masks;
-        if (t < num_tiles) tile_prefix[t] = s_prefix + wave_offset + incl - cnt;
+        if (t < num_tiles) tile_local[t] = wave_offset + incl - cnt;
     }
+    if (tid == 0) {
+        __hip_atomic_store(chunk_total + chunk, total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        s_last = atomicAdd(&hdr->done, 1u) == num_chunks - 1 ? 1u : 0u;
+    }
+    __syncthreads();
+    if (s_last == 0u) return;
+
+    // ---- last workgroup: exclusive scan of the chunk totals
+    __threadfence();
+    unsigned long long carry = 0;
+    for (unsigned base = 0; base < num_chunks; base += kThreads) {
+        const unsigned c = base + tid;
+        const unsigned long long v =
+            c < num_chunks ? __hip_atomic_load(chunk_total + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                           : 0u;
+        unsigned long long inc = v;
+#pragma unroll
+        for (int off = 1; off < kWaveSize; off <<= 1) {
+            const unsigned long long t = __shfl_up(inc, off);
+            if (lane >= off) inc += t;
+        }
+        __syncthreads();   // s_wave_sum of the previous round has been read
+        if (lane == kWaveSize - 1) s_wave_sum[wave] = inc;
+        __syncthreads();
+        unsigned long long before = carry, all = 0;
+#pragma unroll
+        for (int w2 = 0; w2 < kWaves; ++w2) {
+            const unsigned long long t = s_wave_sum[w2];
+            if (w2 < wave) before += t;
+            all += t;
+        }
+        if (c < num_chunks) chunk_prefix[c] = before + inc - v;
+        carry += all;
+    }
+    if (tid == 0) hdr->done = 0u;   // ready for the next call
 }
 
 // Section 5.2 decoder.  values_avail = number of stored elements that may be
@@ -653,7 +686,8 @@ template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
-    const unsigned long long* __restrict__ tile_prefix, size_t num_groups) {
+    const unsigned* __restrict__ tile_local, const unsigned long long* __restrict__ chunk_prefix,
+    size_t num_groups) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -671,7 +705,8 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
     // stored elements in all earlier tiles, from the mask pre-pass
-    const unsigned long long exclusive = uniform(tile_prefix[tile]);
+    const unsigned long long exclusive =
+        uniform(chunk_prefix[tile / (kChunkMasks / G::kTileGroups)]) + uniform(tile_local[tile]);
 
     // ---- MPT consecutive masks per thread: popcount, exclusive scan over the tile
     unsigned m[MPT];
@@ -809,8 +844,10 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const unsigned char* __
         __threadfence();
         const unsigned finished = atomicAdd(&hdr->done, 1u);
         if (finished == gridDim.x - 1) {
-            const unsigned long long total = atomicAdd(&hdr->nnz, 0ull);
+            // last workgroup: report, and leave the accumulators at zero for the next call
+            const unsigned long long total = atomicExch(&hdr->nnz, 0ull);
             *d_bytes = 4ull * num_groups + static_cast<unsigned long long>(W) * total;
+            hdr->done = 0u;
         }
     }
 }
@@ -900,10 +937,10 @@ void launch_compress_as(dim3 grid, hipStream_t stream, const unsigned char* in, 
 template <int W, int LOADS, bool ALIGNED>
 void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
-                          unsigned char* out, const unsigned long long* tile_prefix,
-                          size_t groups) {
+                          unsigned char* out, const unsigned* tile_local,
+                          const unsigned long long* chunk_prefix, size_t groups) {
     hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, tile_prefix, groups);
+                       masks, values, avail, n, out, tile_local, chunk_prefix, groups);
 }
 
 // Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
@@ -1018,8 +1055,7 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
         hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out, 0ull);
         return hip_ok(hipGetLastError());
     }
-    if (zvc_status st = launch_reset(d_ws, 0, stream)) return st;
-    WsHeader* hdr = static_cast<WsHeader*>(d_ws);
+    WsHeader* hdr = static_cast<WsHeader*>(d_ws);   // accumulators are zero between calls
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(n * static_cast<size_t>(w), 16);
@@ -1083,23 +1119,23 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(groups, kChunkMasks);
-    // pre-pass: scan state sized for the chunks; tile offsets after the largest scan state
-    if (zvc_status st = launch_reset(d_ws, scan_state_bytes(chunks), stream)) return st;
+    // pre-pass arrays live where the encoder keeps its scan state and need no reset
+    unsigned char* area = static_cast<unsigned char*>(d_ws) + kHeaderBytes;
+    unsigned long long* chunk_prefix = reinterpret_cast<unsigned long long*>(area);
+    unsigned* chunk_total = reinterpret_cast<unsigned*>(area + div_up(8 * chunks, 256) * 256);
+    unsigned* tile_local = reinterpret_cast<unsigned*>(area + div_up(8 * chunks, 256) * 256 +
+                                                       div_up(4 * chunks, 256) * 256);
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
-    unsigned long long* tile_prefix = reinterpret_cast<unsigned long long*>(
-        static_cast<unsigned char*>(d_ws) + kHeaderBytes +
-        scan_state_bytes(tiles_for(n, w, kMinLoads)));
     const unsigned tile_masks = static_cast<unsigned>(kThreads * 16 * loads / w / 32);
-    const ScanState st = scan_state(d_ws, chunks);
     hipLaunchKernelGGL(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), 0,
                        stream, masks, groups, static_cast<unsigned>(n % 32), tile_masks,
-                       static_cast<unsigned>(tiles), tile_prefix, st.hdr, st.counts, st.prefixes,
-                       g_patience.load(std::memory_order_relaxed));
+                       static_cast<unsigned>(tiles), static_cast<unsigned>(chunks), tile_local,
+                       chunk_total, chunk_prefix, static_cast<WsHeader*>(d_ws));
     if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
     launch_decompress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values,
-                      avail, n, static_cast<unsigned char*>(d_out), tile_prefix, groups);
+                      avail, n, static_cast<unsigned char*>(d_out), tile_local, chunk_prefix, groups);
     return hip_ok(hipGetLastError());
 }
 
