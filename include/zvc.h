@@ -98,16 +98,19 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
  * help at once, which tests use to exercise that path.  Process-wide. */
 void zvc_set_lookback_patience(unsigned polls);
 
-/* Number of times, during the last compress/decompress call on this workspace,
- * that a waiting tile computed a predecessor's count itself.  Synchronous
- * 8-byte device-to-host copy; call it after the stream has drained. */
+/* Number of times, since zvc_workspace_init, that a waiting tile computed a
+ * predecessor's count itself.  Synchronous 8-byte device-to-host copy; call it
+ * after the stream has drained. */
 zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count);
 
 /* ---- device entry points -------------------------------------------------- */
 
 /* Prepare a freshly allocated workspace (fills it with its initial state).
  * Call once per allocation before its first use; ws is the allocation's size
- * in bytes, at least zvc_workspace_bytes(0, 4). */
+ * in bytes, at least zvc_workspace_bytes(0, 4).  Every call leaves the
+ * workspace ready for the next one, so no other reset is ever needed; only
+ * after a call failed with ZVC_E_HIP (or its kernels were aborted) must the
+ * workspace be initialised again. */
 zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream);
 
 /* Count-only pass: *d_bytes = 4*ceil(n/32) + w*nnz, the size zvc_compress would

@@ -37,7 +37,8 @@ namespace {
 constexpr int kThreads = 256;                 // 4 waves of 64 lanes
 constexpr int kWaveSize = 64;
 constexpr int kWaves = kThreads / kWaveSize;
-constexpr size_t kHeaderBytes = 256;          // workspace header, then the scan state
+constexpr int kFinishLanes = 64;              // finish counters, one 128-byte line each
+constexpr size_t kHeaderBytes = 256 + 128 * (kFinishLanes + 1);  // header, then the scan state
 constexpr int kMinLoads = 4;                  // smallest tile: 16 KB (sizes the workspace)
 constexpr int kStageLoads = 4;                // 16-byte loads a wave stages through LDS at a time
 constexpr int kBlockTiles = 64;               // one running prefix is published per 64 tiles
@@ -71,10 +72,16 @@ struct WsHeader {
     unsigned int pad0;
     unsigned long long nnz;        // accumulator of the count-only pass
     unsigned long long size_word;  // compressed size for zvc_offload's read-back
-    unsigned long long helped;     // predecessor counts computed by a waiting tile
+    unsigned long long helped;     // predecessor counts computed by a waiting tile (last encoder call)
     unsigned long long pad[28];
+    // Encoder clean-up: tile t counts itself finished in finish[t % 64] once it
+    // has read all the scan state it needs; the tile that completes a lane
+    // bumps finish_top; the tile that completes finish_top zeroes the scan
+    // state and these counters, so the next call needs no reset kernel.  One
+    // counter per 128-byte line keeps the atomics on one address T/64 apart.
+    struct alignas(128) Line { unsigned value; } finish[kFinishLanes], finish_top;
 };
-static_assert(sizeof(WsHeader) == kHeaderBytes, "header is 256 bytes");
+static_assert(sizeof(WsHeader) == kHeaderBytes, "header size");
 
 // Scan state in the workspace, after the header:
 //   counts[t]   : 32-bit word per tile, top bit = published, rest = the tile's
@@ -95,8 +102,12 @@ inline size_t prefixes_bytes(size_t tiles) { return 8 * div_up(tiles, kBlockTile
 inline size_t scan_state_bytes(size_t tiles) {
     return counts_bytes(tiles) + div_up(prefixes_bytes(tiles), 256) * 256;
 }
-// the decoder's per-tile offsets (64-bit each) follow the scan state of the largest call
-inline size_t tile_prefix_bytes(size_t tiles) { return div_up(8 * tiles, 256) * 256; }
+// the decoder pre-pass arrays follow the encoder's scan state (which is kept
+// zeroed between calls and must not be scribbled on)
+inline size_t pad256(size_t b) { return div_up(b, 256) * 256; }
+inline size_t decoder_area_bytes(size_t tiles, size_t chunks) {
+    return pad256(8 * chunks) + pad256(4 * chunks) + pad256(4 * tiles);
+}
 
 // ------------------------------------------------------------ device helpers
 __device__ inline unsigned long long load64(const unsigned long long* p) {
@@ -381,6 +392,37 @@ __device__ inline unsigned long long tile_exclusive_prefix(unsigned* counts,
     return exclusive;
 }
 
+// Encoder clean-up, see WsHeader::finish.  finish_ticket() is called by lane 0
+// of the scan wave once the tile has read all the scan state it needs and its
+// own words have been written (the s_waitcnt makes the write-through stores
+// complete before the counter moves, so no late store can land after the
+// clean-up).  finish_tile() is called by the same wave at the end of the tile.
+__device__ inline unsigned finish_ticket(WsHeader* hdr, unsigned tile) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    return atomicAdd(&hdr->finish[tile % kFinishLanes].value, 1u);
+}
+
+__device__ inline void finish_tile(WsHeader* hdr, unsigned* counts, unsigned tile,
+                                   unsigned num_tiles, unsigned ticket, int lane,
+                                   size_t state_bytes) {
+    unsigned last = 0;
+    if (lane == 0) {
+        const unsigned slot = tile % kFinishLanes;
+        const unsigned quota = num_tiles / kFinishLanes + (slot < num_tiles % kFinishLanes ? 1u : 0u);
+        if (ticket == quota - 1) {
+            const unsigned slots_used = num_tiles < kFinishLanes ? num_tiles : kFinishLanes;
+            last = atomicAdd(&hdr->finish_top.value, 1u) == slots_used - 1 ? 1u : 0u;
+        }
+    }
+    if (__shfl(last, 0) == 0u) return;
+    // every tile of this call has finished with the scan state: zero it for the next call
+    uint4* p = reinterpret_cast<uint4*>(counts);   // counts then prefixes, 256-byte aligned
+    const size_t chunks = state_bytes / 16;
+    for (size_t i = lane; i < chunks; i += kWaveSize) p[i] = make_uint4(0u, 0u, 0u, 0u);
+    hdr->finish[lane].value = 0u;
+    if (lane == 0) hdr->finish_top.value = 0u;
+}
+
 // Count of non-zero elements of input tile q, by one wave (scan self-help).
 template <int W, int LOADS, bool ALIGNED>
 struct CountInputTile {
@@ -439,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     const unsigned char* __restrict__ in, size_t n, unsigned* __restrict__ masks,
     unsigned char* __restrict__ values, WsHeader* hdr, unsigned* counts,
     unsigned long long* prefixes, unsigned long long* d_bytes, unsigned num_tiles,
-    size_t num_groups, unsigned patience) {
+    size_t num_groups, unsigned patience, size_t state_bytes) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -520,6 +562,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     }
 
     // ---- device-wide exclusive scan, wave 0
+    unsigned ticket = 0;
     if (wave == 0) {
         const CountInputTile<W, LOADS, ALIGNED> count_tile{in, n};
         const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, tile, tile_total,
@@ -528,6 +571,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     }
     __syncthreads();
     const unsigned long long exclusive = uniform(s_prefix);
+    // after the barrier, so that only this wave waits for its state stores to complete;
+    // the counter's answer comes back while the wave does its share of the compaction
+    if (wave == 0 && lane == 0) ticket = finish_ticket(hdr, tile);
 
     // ---- compaction (section 5.2: shift non-zeros to their packed slots).
     //      Each wave stages kStageLoads loads at a time in its own LDS slice in
@@ -568,6 +614,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     // ---- section 5.4: the compressed size, reported by the last tile
     if (tile == num_tiles - 1 && tid == 0)
         *d_bytes = 4ull * num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
+
+    if (wave == 0) finish_tile(hdr, counts, tile, num_tiles, ticket, lane, state_bytes);
 }
 
 // Decoder pre-pass (section 5.2: the popcount of a mask span is the number of
@@ -643,15 +691,15 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
         if (t < num_tiles) tile_local[t] = wave_offset + incl - cnt;
     }
     if (tid == 0) {
+        // write-through store, completed before the counter moves; no cache-wide fence
         __hip_atomic_store(chunk_total + chunk, total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __threadfence();
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         s_last = atomicAdd(&hdr->done, 1u) == num_chunks - 1 ? 1u : 0u;
     }
     __syncthreads();
     if (s_last == 0u) return;
 
-    // ---- last workgroup: exclusive scan of the chunk totals
-    __threadfence();
+    // ---- last workgroup: exclusive scan of the chunk totals (device-scope loads)
     unsigned long long carry = 0;
     for (unsigned base = 0; base < num_chunks; base += kThreads) {
         const unsigned c = base + tid;
@@ -840,8 +888,8 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const unsigned char* __
     if (threadIdx.x == 0) {
         unsigned long long block_total = 0;
         for (int v = 0; v < kWaves; ++v) block_total += s_wave[v];
-        atomicAdd(&hdr->nnz, block_total);
-        __threadfence();
+        const unsigned long long before = atomicAdd(&hdr->nnz, block_total);
+        asm volatile("" : : "v"(before) : "memory");   // performed before the counter moves
         const unsigned finished = atomicAdd(&hdr->done, 1u);
         if (finished == gridDim.x - 1) {
             // last workgroup: report, and leave the accumulators at zero for the next call
@@ -931,7 +979,7 @@ void launch_compress_as(dim3 grid, hipStream_t stream, const unsigned char* in, 
                         unsigned long long* d_bytes, unsigned tiles, size_t groups) {
     hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream, in, n,
                        masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles, groups,
-                       g_patience.load(std::memory_order_relaxed));
+                       g_patience.load(std::memory_order_relaxed), scan_state_bytes(tiles));
 }
 
 template <int W, int LOADS, bool ALIGNED>
@@ -1008,7 +1056,8 @@ size_t zvc_max_compressed_bytes(size_t n, int w) {
 size_t zvc_workspace_bytes(size_t n, int w) {
     if (w != 2 && w != 4) return 0;
     const size_t tiles = tiles_for(n, w, kMinLoads);
-    return kHeaderBytes + scan_state_bytes(tiles) + tile_prefix_bytes(tiles);
+    return kHeaderBytes + scan_state_bytes(tiles) +
+           decoder_area_bytes(tiles, div_up(div_up(n, 32), kChunkMasks));
 }
 
 zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w) {
@@ -1094,7 +1143,7 @@ zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t o
     const int loads = choose_loads(n, w, al);
     const size_t tiles = tiles_for(n, w, loads);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
-    if (zvc_status st = launch_reset(d_ws, scan_state_bytes(tiles), stream)) return st;
+    // the scan state is zero between calls: the kernel cleans up after itself
     const size_t groups = div_up(n, 32);
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
@@ -1119,12 +1168,12 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(groups, kChunkMasks);
-    // pre-pass arrays live where the encoder keeps its scan state and need no reset
-    unsigned char* area = static_cast<unsigned char*>(d_ws) + kHeaderBytes;
+    // pre-pass arrays live after the encoder's scan state and need no reset
+    unsigned char* area = static_cast<unsigned char*>(d_ws) + kHeaderBytes +
+                          scan_state_bytes(tiles_for(n, w, kMinLoads));
     unsigned long long* chunk_prefix = reinterpret_cast<unsigned long long*>(area);
-    unsigned* chunk_total = reinterpret_cast<unsigned*>(area + div_up(8 * chunks, 256) * 256);
-    unsigned* tile_local = reinterpret_cast<unsigned*>(area + div_up(8 * chunks, 256) * 256 +
-                                                       div_up(4 * chunks, 256) * 256);
+    unsigned* chunk_total = reinterpret_cast<unsigned*>(area + pad256(8 * chunks));
+    unsigned* tile_local = reinterpret_cast<unsigned*>(area + pad256(8 * chunks) + pad256(4 * chunks));
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
     const unsigned tile_masks = static_cast<unsigned>(kThreads * 16 * loads / w / 32);
     hipLaunchKernelGGL(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), 0,
