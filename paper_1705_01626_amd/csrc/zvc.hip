@@ -623,89 +623,102 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
 // on the masks alone, which are 1/32 (fp32) or 1/16 (16-bit) of the tensor, so
 // they are computed ahead of the decoder, which then has no dependency between
 // workgroups at all.  One workgroup takes a chunk of kChunkMasks consecutive
-// masks (64 per thread), i.e. a whole number of decoder tiles, and writes
+// masks (a whole number of decoder tiles) with coalesced 16-byte loads and
+// writes
 //   tile_local[t]  = stored elements of the chunk before tile t,
 //   chunk_total[c] = stored elements of the chunk.
-// The workgroup that finishes last (one counter increment per chunk; chunks
-// are 2 MB of fp32 output, so these same-address atomics stay far from their
-// ~11 ns serialisation limit) turns the totals into chunk_prefix[c] and puts
-// the counter back to zero, so the workspace needs no reset between calls.
-constexpr int kChunkMasksPerThread = 64;
-constexpr int kChunkMasks = kThreads * kChunkMasksPerThread;  // 16384 masks = 524288 elements
+// No atomics, no state to reset.  The decoder adds up the totals of the chunks
+// before its own (a few hundred 4-byte words that are already quiet in L2);
+// only for tensors with more than kInlineChunks chunks does a one-workgroup
+// kernel turn the totals into prefixes first.
+constexpr int kChunkLoads = 16;                                // 16-byte loads per thread
+constexpr int kChunkMasks = kThreads * 4 * kChunkLoads;        // 16384 masks = 524288 elements
+constexpr int kUnitMasks = 128;                                // smallest decoder tile, in masks
+constexpr int kChunkUnits = kChunkMasks / kUnitMasks;          // 128
+constexpr size_t kInlineChunks = 4096;
 
 __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     const unsigned* __restrict__ masks, size_t num_groups, unsigned tail, unsigned tile_masks,
-    unsigned num_tiles, unsigned num_chunks, unsigned* __restrict__ tile_local,
-    unsigned* chunk_total, unsigned long long* chunk_prefix, WsHeader* hdr) {
-    __shared__ unsigned s_wave_total[kWaves];
-    __shared__ unsigned long long s_wave_sum[kWaves];
-    __shared__ unsigned s_last;
+    unsigned num_tiles, unsigned* __restrict__ tile_local, unsigned* __restrict__ chunk_total) {
+    __shared__ unsigned s_unit[kChunkUnits];
+    __shared__ unsigned s_wave_total[2];
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid / kWaveSize;
     const unsigned chunk = blockIdx.x;
-    const size_t g0 = static_cast<size_t>(chunk) * kChunkMasks +
-                      static_cast<size_t>(tid) * kChunkMasksPerThread;
+    const size_t g_chunk = static_cast<size_t>(chunk) * kChunkMasks;
 
-    // ---- the thread's 64 masks (256 bytes).  A decoder tile has at least 128
-    //      masks, so a thread's span never straddles a tile start.
-    unsigned cnt = 0;
-    const bool whole = g0 + kChunkMasksPerThread <= num_groups &&
-                       !(g0 + kChunkMasksPerThread == num_groups && tail != 0);
-    if (whole && (reinterpret_cast<uintptr_t>(masks + g0) & 15u) == 0) {
-        const uint4* p = reinterpret_cast<const uint4*>(masks + g0);
+    // ---- load k covers masks [g_chunk + 1024 k, + 1024): 4 per thread, 4 KB per workgroup
+    unsigned c[kChunkLoads];
+    const bool whole = g_chunk + kChunkMasks <= num_groups &&
+                       !(g_chunk + kChunkMasks == num_groups && tail != 0) &&
+                       (reinterpret_cast<uintptr_t>(masks) & 15u) == 0;
+    if (whole) {
 #pragma unroll
-        for (int k = 0; k < kChunkMasksPerThread / 4; ++k) {
-            const uint4 v = load16_stream(p + k);
-            cnt += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+        for (int k = 0; k < kChunkLoads; ++k) {
+            const uint4 v = load16_stream(masks + g_chunk + 1024 * k + 4 * tid);
+            c[k] = __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
         }
     } else {
-        for (int k = 0; k < kChunkMasksPerThread; ++k) {
-            const size_t g = g0 + k;
-            if (g < num_groups) {
-                unsigned m = masks[g];
-                if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;  // bits past n never count
-                cnt += __popc(m);
+#pragma unroll 1
+        for (int k = 0; k < kChunkLoads; ++k) {
+            unsigned sum = 0;
+            for (int i = 0; i < 4; ++i) {
+                const size_t g = g_chunk + 1024 * k + 4 * tid + i;
+                if (g < num_groups) {
+                    unsigned m = masks[g];
+                    if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;  // bits past n never count
+                    sum += __popc(m);
+                }
             }
+            c[k] = sum;
         }
     }
-    unsigned incl = cnt;
+    // ---- a unit is 128 masks = 32 lanes of one load: sums over aligned half-waves,
+    //      two loads packed per register (a unit holds at most 4096 set bits)
+    const int half = tid / 32;   // 0..7: the unit within the load
+#pragma unroll
+    for (int q = 0; q < kChunkLoads / 2; ++q) {
+        unsigned p = c[2 * q] | (c[2 * q + 1] << 16);
+#pragma unroll
+        for (int off = 1; off < 32; off <<= 1) p += __shfl_xor(p, off);
+        if ((lane & 31) == 0) {
+            s_unit[(2 * q) * 8 + half] = p & 0xFFFFu;
+            s_unit[(2 * q + 1) * 8 + half] = p >> 16;
+        }
+    }
+    __syncthreads();
+    // ---- exclusive scan of the 128 unit sums (waves 0 and 1)
+    const unsigned v = tid < kChunkUnits ? s_unit[tid] : 0u;
+    unsigned incl = v;
 #pragma unroll
     for (int off = 1; off < kWaveSize; off <<= 1) {
         const unsigned t = __shfl_up(incl, off);
         if (lane >= off) incl += t;
     }
-    if (lane == kWaveSize - 1) s_wave_total[wave] = incl;
+    if (lane == kWaveSize - 1 && wave < 2) s_wave_total[wave] = incl;
     __syncthreads();
-    unsigned wave_offset = 0, total = 0;
-#pragma unroll
-    for (int v = 0; v < kWaves; ++v) {
-        const unsigned t = s_wave_total[v];
-        if (v < wave) wave_offset += t;
-        total += t;
+    const unsigned excl = incl - v + (wave == 1 ? s_wave_total[0] : 0u);
+    const unsigned units_per_tile = tile_masks / kUnitMasks;
+    if (tid < kChunkUnits && tid % units_per_tile == 0) {
+        const size_t t = static_cast<size_t>(chunk) * (kChunkMasks / tile_masks) + tid / units_per_tile;
+        if (t < num_tiles) tile_local[t] = excl;
     }
-    // thread tid starts a decoder tile when its first mask is a multiple of tile_masks
-    const unsigned threads_per_tile = tile_masks / kChunkMasksPerThread;
-    if (tid % threads_per_tile == 0) {
-        const size_t t = g0 / tile_masks;
-        if (t < num_tiles) tile_local[t] = wave_offset + incl - cnt;
-    }
-    if (tid == 0) {
-        // write-through store, completed before the counter moves; no cache-wide fence
-        __hip_atomic_store(chunk_total + chunk, total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        s_last = atomicAdd(&hdr->done, 1u) == num_chunks - 1 ? 1u : 0u;
-    }
-    __syncthreads();
-    if (s_last == 0u) return;
+    if (tid == 0) chunk_total[chunk] = s_wave_total[0] + s_wave_total[1];
+}
 
-    // ---- last workgroup: exclusive scan of the chunk totals (device-scope loads)
+// Exclusive prefix of the chunk totals by one workgroup (very large tensors only).
+__global__ __launch_bounds__(kThreads) void chunk_scan_kernel(const unsigned* __restrict__ chunk_total,
+                                                              unsigned long long* __restrict__ chunk_prefix,
+                                                              size_t num_chunks) {
+    __shared__ unsigned long long s_wave_sum[kWaves];
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid / kWaveSize;
     unsigned long long carry = 0;
-    for (unsigned base = 0; base < num_chunks; base += kThreads) {
-        const unsigned c = base + tid;
-        const unsigned long long v =
-            c < num_chunks ? __hip_atomic_load(chunk_total + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                           : 0u;
+    for (size_t base = 0; base < num_chunks; base += kThreads) {
+        const size_t c = base + tid;
+        const unsigned long long v = c < num_chunks ? chunk_total[c] : 0u;
         unsigned long long inc = v;
 #pragma unroll
         for (int off = 1; off < kWaveSize; off <<= 1) {
@@ -725,7 +738,6 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
         if (c < num_chunks) chunk_prefix[c] = before + inc - v;
         carry += all;
     }
-    if (tid == 0) hdr->done = 0u;   // ready for the next call
 }
 
 // Section 5.2 decoder.  values_avail = number of stored elements that may be
@@ -734,8 +746,8 @@ template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
-    const unsigned* __restrict__ tile_local, const unsigned long long* __restrict__ chunk_prefix,
-    size_t num_groups) {
+    const unsigned* __restrict__ tile_local, const unsigned* __restrict__ chunk_total,
+    const unsigned long long* __restrict__ chunk_prefix, size_t num_groups) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -746,15 +758,39 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     __shared__ unsigned s_mask[G::kTileGroups];
     __shared__ unsigned s_group_offset[G::kTileGroups + 1];  // last entry = tile total
     __shared__ unsigned s_wave_total[kWaves];
+    __shared__ unsigned long long s_chunk_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
-    // stored elements in all earlier tiles, from the mask pre-pass
-    const unsigned long long exclusive =
-        uniform(chunk_prefix[tile / (kChunkMasks / G::kTileGroups)]) + uniform(tile_local[tile]);
+    // stored elements in the chunks before this tile's chunk: from the pre-pass
+    // totals (summed here by wave 0) or, for very large tensors, ready-made
+    const unsigned chunk = tile / (kChunkMasks / G::kTileGroups);
+    if (wave == 0) {
+        unsigned long long before = 0;
+        if (chunk_prefix != nullptr) {
+            before = chunk_prefix[chunk];
+        } else {
+            // 256 totals per round (16 bytes per lane), two rounds in flight
+            unsigned long long part = 0;
+            const uint4* totals = reinterpret_cast<const uint4*>(chunk_total);  // 256-byte aligned
+#pragma unroll 1
+            for (unsigned c0 = 0; c0 < chunk; c0 += 8 * kWaveSize) {
+                const unsigned ca = c0 + 4 * lane, cb = ca + 4 * kWaveSize;
+                uint4 va = make_uint4(0u, 0u, 0u, 0u), vb = va;
+                if (ca < chunk) va = totals[ca / 4];
+                if (cb < chunk) vb = totals[cb / 4];
+                part += (ca + 0 < chunk ? va.x : 0u) + (ca + 1 < chunk ? va.y : 0u);
+                part += (ca + 2 < chunk ? va.z : 0u) + (ca + 3 < chunk ? va.w : 0u);
+                part += (cb + 0 < chunk ? vb.x : 0u) + (cb + 1 < chunk ? vb.y : 0u);
+                part += (cb + 2 < chunk ? vb.z : 0u) + (cb + 3 < chunk ? vb.w : 0u);
+            }
+            before = wave_sum(part);
+        }
+        if (lane == 0) s_chunk_prefix = before;
+    }
 
     // ---- MPT consecutive masks per thread: popcount, exclusive scan over the tile
     unsigned m[MPT];
@@ -801,6 +837,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     }
 
     __syncthreads();
+    const unsigned long long exclusive = uniform(s_chunk_prefix) + uniform(tile_local[tile]);
     const bool full_tile = ALIGNED && tile_elem0 + G::kTileElems <= n;
 
     // ---- expand (section 5.2: payload words or zeros muxed into place).  Each
@@ -945,6 +982,7 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
 // itself.  A poll is one memory round trip (about a microsecond).
 constexpr unsigned kDefaultPatience = 2000;
 std::atomic<unsigned> g_patience{kDefaultPatience};
+std::atomic<size_t> g_inline_chunks{kInlineChunks};
 
 // Tile size of the encoder.  Each tile costs a fixed few nanoseconds of
 // chip-wide time (workgroup launch plus the scan's state traffic), so large
@@ -986,9 +1024,10 @@ template <int W, int LOADS, bool ALIGNED>
 void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
                           unsigned char* out, const unsigned* tile_local,
-                          const unsigned long long* chunk_prefix, size_t groups) {
+                          const unsigned* chunk_total, const unsigned long long* chunk_prefix,
+                          size_t groups) {
     hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, tile_local, chunk_prefix, groups);
+                       masks, values, avail, n, out, tile_local, chunk_total, chunk_prefix, groups);
 }
 
 // Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
@@ -1087,6 +1126,10 @@ void zvc_set_lookback_patience(unsigned polls) {
     g_patience.store(polls, std::memory_order_relaxed);
 }
 
+void zvc_set_decoder_inline_chunks(size_t chunks) {
+    g_inline_chunks.store(chunks, std::memory_order_relaxed);
+}
+
 zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count) {
     if (d_ws == nullptr || h_count == nullptr) return ZVC_E_ARG;
     const WsHeader* hdr = static_cast<const WsHeader*>(d_ws);
@@ -1178,13 +1221,20 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     const unsigned tile_masks = static_cast<unsigned>(kThreads * 16 * loads / w / 32);
     hipLaunchKernelGGL(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), 0,
                        stream, masks, groups, static_cast<unsigned>(n % 32), tile_masks,
-                       static_cast<unsigned>(tiles), static_cast<unsigned>(chunks), tile_local,
-                       chunk_total, chunk_prefix, static_cast<WsHeader*>(d_ws));
+                       static_cast<unsigned>(tiles), tile_local, chunk_total);
     if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
+    const unsigned long long* ready_prefix = nullptr;
+    if (chunks > g_inline_chunks.load(std::memory_order_relaxed)) {
+        hipLaunchKernelGGL(chunk_scan_kernel, dim3(1), dim3(kThreads), 0, stream, chunk_total,
+                           chunk_prefix, chunks);
+        if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
+        ready_prefix = chunk_prefix;
+    }
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
     launch_decompress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values,
-                      avail, n, static_cast<unsigned char*>(d_out), tile_local, chunk_prefix, groups);
+                      avail, n, static_cast<unsigned char*>(d_out), tile_local, chunk_total,
+                      ready_prefix, groups);
     return hip_ok(hipGetLastError());
 }
 

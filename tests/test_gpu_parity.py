@@ -244,3 +244,15 @@ def test_no_self_help_in_normal_runs(oracle):
     torch.cuda.synchronize()
     assert zvc.zvc_workspace_self_help_count(ws) == 0
     assert torch.equal(out, x)
+
+
+def test_decoder_with_prefixed_chunk_totals(oracle):
+    """The path for tensors past 2^31 elements (chunk totals prefixed by a
+    one-workgroup kernel), forced on tensors of ordinary size."""
+    try:
+        zvc.zvc_set_decoder_inline_chunks(0)
+        for w, n in ((4, 3000001), (2, 40000003), (4, 1000)):
+            x = random_tensor(n, w, 0.33, seed=w * n)
+            assert_parity(x, oracle, "prefixed chunk totals")
+    finally:
+        zvc.zvc_set_decoder_inline_chunks(4096)
