@@ -98,13 +98,6 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
  * help at once, which tests use to exercise that path.  Process-wide. */
 void zvc_set_lookback_patience(unsigned polls);
 
-/* The decoder's pre-pass splits the masks into chunks of 16384 and gives the
- * stored-element total of each; the decoder adds up the totals before its own
- * chunk unless there are more than `chunks` of them (default 4096, i.e. past
- * 2^31 elements), in which case a one-workgroup kernel prefixes them first.
- * Tests set 0 to exercise that kernel on small tensors.  Process-wide. */
-void zvc_set_decoder_inline_chunks(size_t chunks);
-
 /* Number of times, since zvc_workspace_init, that a waiting tile computed a
  * predecessor's count itself.  Synchronous 8-byte device-to-host copy; call it
  * after the stream has drained. */

@@ -59,10 +59,8 @@ struct Geometry {
     static constexpr int kMasksPerThread = kTileGroups > kThreads ? kTileGroups / kThreads : 1;
     // per-wave LDS staging buffer: kStageLoads wave-loads plus alignment slack
     static constexpr int kStageSteps = LOADS / kStageLoads;
-    // (16 bytes so the slice can mirror the destination's alignment) and one
-    // 4-byte dump word per lane for elements that are not kept
-    static constexpr int kDumpOffset = kStageLoads * kWaveSize * 16 + 16;
-    static constexpr int kWaveStageBytes = kDumpOffset + 4 * kWaveSize;
+    // (16 bytes so the slice can mirror the destination's alignment)
+    static constexpr int kWaveStageBytes = kStageLoads * kWaveSize * 16 + 16;
     static_assert(LOADS % kStageLoads == 0, "tile is staged in whole steps");
 };
 
@@ -74,11 +72,13 @@ struct WsHeader {
     unsigned long long size_word;  // compressed size for zvc_offload's read-back
     unsigned long long helped;     // predecessor counts computed by a waiting tile (last encoder call)
     unsigned long long pad[28];
-    // Encoder clean-up: tile t counts itself finished in finish[t % 64] once it
-    // has read all the scan state it needs; the tile that completes a lane
-    // bumps finish_top; the tile that completes finish_top zeroes the scan
-    // state and these counters, so the next call needs no reset kernel.  One
-    // counter per 128-byte line keeps the atomics on one address T/64 apart.
+    // Arrival counters, shared by the encoder and the decoder's pre-pass (calls
+    // on one workspace do not overlap).  Encoder: tile t counts itself finished
+    // in finish[t % 64] once it has read all the scan state it needs; the tile
+    // that completes a lane bumps finish_top; the tile that completes finish_top
+    // zeroes the scan state and these counters, so the next call needs no reset
+    // kernel.  One counter per 128-byte line keeps the atomics on one address
+    // T/64 apart.
     struct alignas(128) Line { unsigned value; } finish[kFinishLanes], finish_top;
 };
 static_assert(sizeof(WsHeader) == kHeaderBytes, "header size");
@@ -105,11 +105,25 @@ inline size_t scan_state_bytes(size_t tiles) {
 // the decoder pre-pass arrays follow the encoder's scan state (which is kept
 // zeroed between calls and must not be scribbled on)
 inline size_t pad256(size_t b) { return div_up(b, 256) * 256; }
-inline size_t decoder_area_bytes(size_t tiles, size_t chunks) {
-    return pad256(8 * chunks) + pad256(4 * chunks) + pad256(4 * tiles);
+inline size_t decoder_area_bytes(size_t chunks) {   // chunk_prefix, chunk_total, unit_end
+    return pad256(8 * chunks) + pad256(4 * chunks) + pad256(4 * 128 * chunks);
 }
 
 // ------------------------------------------------------------ device helpers
+// Developer instrumentation, compiled in with -DZVC_TRACE only: lane 0 of a
+// tile's first wave stamps the device-wide 100 MHz clock at a few points into a
+// caller-provided buffer of 8 words per tile (zvc_trace_set).
+#ifdef ZVC_TRACE
+__device__ unsigned long long* g_trace_words;
+#define ZVC_TRACE_POINT(tile, k)                                                          \
+    do {                                                                                  \
+        if (threadIdx.x == 0 && g_trace_words != nullptr)                                 \
+            g_trace_words[static_cast<size_t>(tile) * 8 + (k)] = wall_clock64();          \
+    } while (0)
+#else
+#define ZVC_TRACE_POINT(tile, k) do { } while (0)
+#endif
+
 __device__ inline unsigned long long load64(const unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -178,13 +192,29 @@ __device__ inline void wave_lds_sync() {
 }
 
 // 16 bytes of input for the lane whose first element is e0.  Elements at or
-// past n read as zero.  The 16-byte access is used only when the base pointer
-// is 16-byte aligned (ALIGNED) and the whole chunk is inside the tensor.
+// past n read as zero.  With a 16-byte aligned base (ALIGNED) a chunk that holds
+// at least one element of the tensor is loaded whole: an aligned 16-byte chunk
+// never straddles a page, so the access is as safe as the load of its first
+// element, and the bytes past the tensor's end are cleared in registers.
 template <int W, bool ALIGNED>
 __device__ inline uint4 load_chunk(const unsigned char* __restrict__ in, size_t e0, size_t n) {
     constexpr int E = 16 / W;
-    if (ALIGNED && e0 + E <= n) return load16_stream(in + e0 * W);
     unsigned d[4] = {0u, 0u, 0u, 0u};
+    if (ALIGNED) {
+        if (e0 >= n) return make_uint4(0u, 0u, 0u, 0u);
+        const uint4 v = load16_stream(in + e0 * W);
+        if (e0 + E <= n) return v;
+        const unsigned valid_bytes = static_cast<unsigned>(n - e0) * W;   // 1 .. 15
+        const unsigned raw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned lo = 4u * k;
+            d[k] = valid_bytes >= lo + 4u ? raw[k]
+                 : valid_bytes > lo      ? raw[k] & ((1u << (8u * (valid_bytes - lo))) - 1u)
+                                         : 0u;
+        }
+        return make_uint4(d[0], d[1], d[2], d[3]);
+    }
     if (W == 4) {
         const unsigned* p = reinterpret_cast<const unsigned*>(in);
 #pragma unroll
@@ -443,27 +473,6 @@ struct CountInputTile {
     }
 };
 
-// Count of set mask bits of tile q, by one wave (scan self-help, decoder).
-struct CountMaskTile {
-    const unsigned* masks;
-    size_t num_groups;
-    unsigned tail;        // n % 32
-    int tile_groups;
-    __device__ unsigned operator()(unsigned q, int lane) const {
-        unsigned long long count = 0;
-#pragma unroll 1
-        for (int gi = lane; gi < tile_groups; gi += kWaveSize) {
-            const size_t g = static_cast<size_t>(q) * tile_groups + gi;
-            if (g < num_groups) {
-                unsigned m = masks[g];
-                if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;
-                count += __popc(m);
-            }
-        }
-        return static_cast<unsigned>(wave_sum(count));
-    }
-};
-
 // ------------------------------------------------------------------- kernels
 
 // Zeroes the workspace header and scan state (`words` 8-byte words).
@@ -475,13 +484,54 @@ __global__ void reset_kernel(unsigned long long* ws_words, size_t words) {
 
 __global__ void write_word_kernel(unsigned long long* dst, unsigned long long v) { *dst = v; }
 
+// Workgroup barrier that orders LDS traffic only (__syncthreads() would also
+// wait for the wave's outstanding global stores).
+__device__ inline void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+struct EncoderArgs {
+    const unsigned char* __restrict__ in;
+    size_t n;
+    unsigned* __restrict__ masks;
+    unsigned char* __restrict__ values;
+    WsHeader* hdr;
+    unsigned* counts;
+    unsigned long long* prefixes;
+    unsigned long long* d_bytes;
+    unsigned num_tiles;
+    size_t num_groups;
+    unsigned patience;
+    size_t state_bytes;
+};
+
+// Issues the loads of `tile`: LOADS x 16 bytes per lane, 1 KB per wave
+// instruction.  A tile that lies wholly inside an aligned tensor needs no
+// bounds checks.
+template <int W, int LOADS, bool ALIGNED>
+__device__ __forceinline__ void load_tile(uint4 (&data)[LOADS], const EncoderArgs& a, unsigned tile,
+                                          int wave, int lane) {
+    using G = Geometry<W, LOADS>;
+    constexpr int E = G::kElemsPerLane;
+    const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
+    if (ALIGNED && tile_elem0 + G::kTileElems <= a.n) {
+        const uint4* wave_base = reinterpret_cast<const uint4*>(a.in + tile_elem0 * W) +
+                                 static_cast<size_t>(wave) * LOADS * kWaveSize;
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) data[j] = load16_stream(wave_base + j * kWaveSize + lane);
+    } else {
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const size_t e0 =
+                tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
+            data[j] = load_chunk<W, ALIGNED>(a.in, e0, a.n);
+        }
+    }
+}
+
 // Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.
 template <int W, int LOADS, bool ALIGNED>
-__global__ __launch_bounds__(kThreads) void compress_kernel(
-    const unsigned char* __restrict__ in, size_t n, unsigned* __restrict__ masks,
-    unsigned char* __restrict__ values, WsHeader* hdr, unsigned* counts,
-    unsigned long long* prefixes, unsigned long long* d_bytes, unsigned num_tiles,
-    size_t num_groups, unsigned patience, size_t state_bytes) {
+__global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -494,24 +544,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
-    const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
+    ZVC_TRACE_POINT(tile, 0);
 
-    // ---- load: LOADS x 16 bytes per lane, 1 KB per wave instruction.  A tile
-    //      that lies wholly inside an aligned tensor needs no bounds checks.
-    uint4 data[LOADS];
-    if (ALIGNED && tile_elem0 + G::kTileElems <= n) {
-        const uint4* wave_base = reinterpret_cast<const uint4*>(in + tile_elem0 * W) +
-                                 static_cast<size_t>(wave) * LOADS * kWaveSize;
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) data[j] = load16_stream(wave_base + j * kWaveSize + lane);
-    } else {
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const size_t e0 =
-                tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
-            data[j] = load_chunk<W, ALIGNED>(in, e0, n);
-        }
-    }
+    uint4 cur[LOADS];
+    load_tile<W, LOADS, ALIGNED>(cur, a, tile, wave, lane);
 
     // ---- zero test, in-wave ranks (section 5.2: prefix sum over the mask bits), masks
     unsigned below16[LOADS / 2];     // kept elements of lower lanes in the same load, 16 bits each
@@ -527,18 +563,26 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
         unsigned bits = 0, below = 0, load_total = 0;
 #pragma unroll
         for (int c = 0; c < E; ++c) {
-            const bool nz = element_nonzero<W>(data[j], c);
+            const bool nz = element_nonzero<W>(cur[j], c);
             const unsigned long long b = __ballot(nz);
             below = lanes_below(b, below);
             load_total += static_cast<unsigned>(__popcll(b));
             bits |= (nz ? 1u : 0u) << c;
         }
+        // Pin the rank and the total here and keep the loads' code apart (below).
+        // Left alone the compiler postpones the mbcnt chains until the compaction,
+        // or hoists the compares of all loads, and keeps every ballot of the tile
+        // alive at once, which costs two lane-spills per ballot.
         below16[j / 2] |= below << (16 * (j % 2));
+        asm volatile("" : "+v"(below16[j / 2]), "+s"(load_total));
         run[j + 1] = run[j] + load_total;
         // the group's mask: OR of the lanes' bit fields, each at its position
         const unsigned m = group_or<LPG>(bits << field_shift);
         if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
+        __builtin_amdgcn_sched_barrier(0);
+        if (j == 0) ZVC_TRACE_POINT(tile, 1);
     }
+    ZVC_TRACE_POINT(tile, 2);
 #pragma unroll
     for (int q = 0; q < G::kMaskRegs; ++q) {
         const int j = q * LPG + lane_in_group;  // the load whose mask this lane kept
@@ -546,13 +590,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
             const size_t g = static_cast<size_t>(tile) * G::kTileGroups +
                              static_cast<size_t>(wave * LOADS + j) * G::kGroupsPerLoad +
                              lane / LPG;
-            if (g < num_groups) __builtin_nontemporal_store(my_mask[q], masks + g);
+            if (g < a.num_groups) __builtin_nontemporal_store(my_mask[q], a.masks + g);
         }
     }
-
     // ---- tile-level scan of the wave totals
     if (lane == 0) s_wave_total[wave] = run[LOADS];
-    __syncthreads();
+    lds_barrier();
+    ZVC_TRACE_POINT(tile, 3);
     unsigned wave_offset = 0, tile_total = 0;
 #pragma unroll
     for (int v = 0; v < kWaves; ++v) {
@@ -564,84 +608,88 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     // ---- device-wide exclusive scan, wave 0
     unsigned ticket = 0;
     if (wave == 0) {
-        const CountInputTile<W, LOADS, ALIGNED> count_tile{in, n};
-        const unsigned long long ex = tile_exclusive_prefix(counts, prefixes, tile, tile_total,
-                                                            lane, patience, hdr, count_tile);
+        const CountInputTile<W, LOADS, ALIGNED> count_tile{a.in, a.n};
+        const unsigned long long ex = tile_exclusive_prefix(a.counts, a.prefixes, tile, tile_total,
+                                                            lane, a.patience, a.hdr, count_tile);
         if (lane == 0) s_prefix = ex;
+        ZVC_TRACE_POINT(tile, 4);
     }
-    __syncthreads();
+    lds_barrier();
     const unsigned long long exclusive = uniform(s_prefix);
     // after the barrier, so that only this wave waits for its state stores to complete;
     // the counter's answer comes back while the wave does its share of the compaction
-    if (wave == 0 && lane == 0) ticket = finish_ticket(hdr, tile);
+    if (wave == 0 && lane == 0) ticket = finish_ticket(a.hdr, tile);
 
     // ---- compaction (section 5.2: shift non-zeros to their packed slots).
     //      Each wave stages kStageLoads loads at a time in its own LDS slice in
     //      packed order, then copies the run out.  LDS byte p of the slice
     //      corresponds to global byte (dst - shift) + p, so 16-byte chunks are
-    //      aligned on both sides.  Elements that are not kept go to a per-lane
-    //      dump word: every lane issues every LDS write, no branches.
+    //      aligned on both sides.
     unsigned char* stage = s_stage[wave];
-    const unsigned dump = G::kDumpOffset + 4u * lane;
 #pragma unroll
     for (int h = 0; h < G::kStageSteps; ++h) {
         const unsigned first_rank = run[h * kStageLoads];
         const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
-        unsigned char* dst = values + (exclusive + wave_offset + first_rank) * W;  // wave-uniform
+        unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W;  // wave-uniform
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
 #pragma unroll
         for (int jj = 0; jj < kStageLoads; ++jj) {
             const int j = h * kStageLoads + jj;
-            unsigned a = shift + W * ((run[j] - first_rank) +
-                                      ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu));
+            unsigned char* at = stage + (shift + W * (run[j] - first_rank)) +
+                                W * ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
 #pragma unroll
             for (int c = 0; c < E; ++c) {
-                const bool nz = element_nonzero<W>(data[j], c);
-                const unsigned at = nz ? a : dump;
-                const unsigned v = element_of<W>(data[j], c);
-                if (W == 4)
-                    *reinterpret_cast<unsigned*>(stage + at) = v;
-                else
-                    *reinterpret_cast<unsigned short*>(stage + at) = static_cast<unsigned short>(v);
-                a += nz ? W : 0;
+                const bool nz = element_nonzero<W>(cur[j], c);
+                const unsigned v = element_of<W>(cur[j], c);
+                if (__builtin_expect(nz, 1)) {   // predicated: write and advance in the kept lanes only
+                    if (W == 4)
+                        *reinterpret_cast<unsigned*>(at) = v;
+                    else
+                        *reinterpret_cast<unsigned short*>(at) = static_cast<unsigned short>(v);
+                    at += W;
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
         wave_lds_sync();
         wave_copy_out<W>(dst - shift, stage, shift, shift + step_total * W, lane);
         wave_lds_sync();
     }
+    ZVC_TRACE_POINT(tile, 5);
 
     // ---- section 5.4: the compressed size, reported by the last tile
-    if (tile == num_tiles - 1 && tid == 0)
-        *d_bytes = 4ull * num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
+    if (tile == a.num_tiles - 1 && tid == 0)
+        *a.d_bytes = 4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
 
-    if (wave == 0) finish_tile(hdr, counts, tile, num_tiles, ticket, lane, state_bytes);
+    if (wave == 0) finish_tile(a.hdr, a.counts, tile, a.num_tiles, ticket, lane, a.state_bytes);
 }
 
 // Decoder pre-pass (section 5.2: the popcount of a mask span is the number of
-// stored words the span consumes).  The offsets of the decoder's tiles depend
-// on the masks alone, which are 1/32 (fp32) or 1/16 (16-bit) of the tensor, so
-// they are computed ahead of the decoder, which then has no dependency between
-// workgroups at all.  One workgroup takes a chunk of kChunkMasks consecutive
-// masks (a whole number of decoder tiles) with coalesced 16-byte loads and
-// writes
-//   tile_local[t]  = stored elements of the chunk before tile t,
+// stored words the span consumes).  Where a span's stored elements start
+// depends on the masks alone, which are 1/32 (fp32) or 1/16 (16-bit) of the
+// tensor, so it is computed ahead of the decoder, whose waves then depend on
+// nothing but their own part of the stream.  One workgroup takes a chunk of
+// kChunkMasks consecutive masks with coalesced 16-byte loads and writes
+//   unit_end[u]    = stored elements of the chunk up to and including unit u
+//                    (a unit is 32 masks, 1024 elements),
 //   chunk_total[c] = stored elements of the chunk.
-// No atomics, no state to reset.  The decoder adds up the totals of the chunks
-// before its own (a few hundred 4-byte words that are already quiet in L2);
-// only for tensors with more than kInlineChunks chunks does a one-workgroup
-// kernel turn the totals into prefixes first.
-constexpr int kChunkLoads = 16;                                // 16-byte loads per thread
-constexpr int kChunkMasks = kThreads * 4 * kChunkLoads;        // 16384 masks = 524288 elements
-constexpr int kUnitMasks = 128;                                // smallest decoder tile, in masks
+// The workgroup that finishes last (arrival counters in the header, which it
+// also resets) turns the totals into chunk_prefix[c] = stored elements before
+// chunk c.
+constexpr int kUnitMasks = 32;
+constexpr int kChunkLoads = 4;                                 // 16-byte loads per thread
+constexpr int kChunkMasks = kThreads * 4 * kChunkLoads;        // 4096 masks = 131072 elements
 constexpr int kChunkUnits = kChunkMasks / kUnitMasks;          // 128
-constexpr size_t kInlineChunks = 4096;
+constexpr int kUnitLanes = kUnitMasks / 4;                     // 8 lanes of one load cover a unit
 
 __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
-    const unsigned* __restrict__ masks, size_t num_groups, unsigned tail, unsigned tile_masks,
-    unsigned num_tiles, unsigned* __restrict__ tile_local, unsigned* __restrict__ chunk_total) {
+    const unsigned* __restrict__ masks, size_t num_groups, unsigned tail,
+    unsigned* __restrict__ unit_end, unsigned* chunk_total,
+    unsigned long long* __restrict__ chunk_prefix, WsHeader* hdr, unsigned num_chunks) {
     __shared__ unsigned s_unit[kChunkUnits];
     __shared__ unsigned s_wave_total[2];
+    __shared__ unsigned long long s_wave_sum[kWaves];
+    __shared__ unsigned s_last;
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = tid / kWaveSize;
@@ -674,21 +722,20 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
             c[k] = sum;
         }
     }
-    // ---- a unit is 128 masks = 32 lanes of one load: sums over aligned half-waves,
-    //      two loads packed per register (a unit holds at most 4096 set bits)
-    const int half = tid / 32;   // 0..7: the unit within the load
+    // ---- unit sums: 8 consecutive lanes of one load, two loads packed per register
+    //      (a unit holds at most 1024 set bits)
 #pragma unroll
     for (int q = 0; q < kChunkLoads / 2; ++q) {
         unsigned p = c[2 * q] | (c[2 * q + 1] << 16);
 #pragma unroll
-        for (int off = 1; off < 32; off <<= 1) p += __shfl_xor(p, off);
-        if ((lane & 31) == 0) {
-            s_unit[(2 * q) * 8 + half] = p & 0xFFFFu;
-            s_unit[(2 * q + 1) * 8 + half] = p >> 16;
+        for (int off = 1; off < kUnitLanes; off <<= 1) p += __shfl_xor(p, off);
+        if (tid % kUnitLanes == 0) {
+            s_unit[(2 * q) * (kThreads / kUnitLanes) + tid / kUnitLanes] = p & 0xFFFFu;
+            s_unit[(2 * q + 1) * (kThreads / kUnitLanes) + tid / kUnitLanes] = p >> 16;
         }
     }
     __syncthreads();
-    // ---- exclusive scan of the 128 unit sums (waves 0 and 1)
+    // ---- inclusive scan of the 128 unit sums (waves 0 and 1)
     const unsigned v = tid < kChunkUnits ? s_unit[tid] : 0u;
     unsigned incl = v;
 #pragma unroll
@@ -698,192 +745,170 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     }
     if (lane == kWaveSize - 1 && wave < 2) s_wave_total[wave] = incl;
     __syncthreads();
-    const unsigned excl = incl - v + (wave == 1 ? s_wave_total[0] : 0u);
-    const unsigned units_per_tile = tile_masks / kUnitMasks;
-    if (tid < kChunkUnits && tid % units_per_tile == 0) {
-        const size_t t = static_cast<size_t>(chunk) * (kChunkMasks / tile_masks) + tid / units_per_tile;
-        if (t < num_tiles) tile_local[t] = excl;
-    }
-    if (tid == 0) chunk_total[chunk] = s_wave_total[0] + s_wave_total[1];
-}
+    if (tid < kChunkUnits)
+        unit_end[static_cast<size_t>(chunk) * kChunkUnits + tid] =
+            incl + (wave == 1 ? s_wave_total[0] : 0u);
 
-// Exclusive prefix of the chunk totals by one workgroup (very large tensors only).
-__global__ __launch_bounds__(kThreads) void chunk_scan_kernel(const unsigned* __restrict__ chunk_total,
-                                                              unsigned long long* __restrict__ chunk_prefix,
-                                                              size_t num_chunks) {
-    __shared__ unsigned long long s_wave_sum[kWaves];
-    const int tid = threadIdx.x;
-    const int lane = tid & (kWaveSize - 1);
-    const int wave = tid / kWaveSize;
+    // ---- the last workgroup to get here prefixes the chunk totals
+    if (tid == 0) {
+        store32(chunk_total + chunk, s_wave_total[0] + s_wave_total[1]);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the total is out before the count moves
+        // counted like the encoder's tiles: atomics on one address cost about 11 ns
+        // each here, so the arrivals are spread over 64 counters with one on top
+        const unsigned slot = chunk % kFinishLanes;
+        const unsigned quota = num_chunks / kFinishLanes + (slot < num_chunks % kFinishLanes ? 1u : 0u);
+        unsigned last = 0;
+        if (atomicAdd(&hdr->finish[slot].value, 1u) == quota - 1) {
+            const unsigned slots_used = num_chunks < kFinishLanes ? num_chunks : kFinishLanes;
+            last = atomicAdd(&hdr->finish_top.value, 1u) == slots_used - 1 ? 1u : 0u;
+        }
+        s_last = last;
+    }
+    __syncthreads();
+    if (s_last == 0u) return;
+    // 8 consecutive totals per thread and round, all loads of a round in flight together
+    constexpr int kPerThread = 8;
     unsigned long long carry = 0;
-    for (size_t base = 0; base < num_chunks; base += kThreads) {
-        const size_t c = base + tid;
-        const unsigned long long v = c < num_chunks ? chunk_total[c] : 0u;
-        unsigned long long inc = v;
+    for (size_t base = 0; base < num_chunks; base += kThreads * kPerThread) {
+        const size_t c0 = base + static_cast<size_t>(tid) * kPerThread;   // chunk_total is 256-byte aligned
+        unsigned long long pair[kPerThread / 2];
+#pragma unroll
+        for (int k = 0; k < kPerThread / 2; ++k)
+            pair[k] = c0 + 2 * k < num_chunks
+                          ? load64(reinterpret_cast<const unsigned long long*>(chunk_total + c0 + 2 * k))
+                          : 0ull;
+        unsigned t[kPerThread];
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            t[k] = c0 + k < num_chunks ? static_cast<unsigned>(pair[k / 2] >> (32 * (k % 2))) : 0u;
+            mine += t[k];
+        }
+        unsigned long long inc = mine;
 #pragma unroll
         for (int off = 1; off < kWaveSize; off <<= 1) {
-            const unsigned long long t = __shfl_up(inc, off);
-            if (lane >= off) inc += t;
+            const unsigned long long up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
         }
         __syncthreads();   // s_wave_sum of the previous round has been read
         if (lane == kWaveSize - 1) s_wave_sum[wave] = inc;
         __syncthreads();
-        unsigned long long before = carry, all = 0;
+        unsigned long long before = carry + inc - mine, all = 0;
 #pragma unroll
         for (int w2 = 0; w2 < kWaves; ++w2) {
-            const unsigned long long t = s_wave_sum[w2];
-            if (w2 < wave) before += t;
-            all += t;
+            const unsigned long long ws = s_wave_sum[w2];
+            if (w2 < wave) before += ws;
+            all += ws;
         }
-        if (c < num_chunks) chunk_prefix[c] = before + inc - v;
+#pragma unroll
+        for (int k = 0; k < kPerThread; ++k) {
+            if (c0 + k < num_chunks) chunk_prefix[c0 + k] = before;
+            before += t[k];
+        }
         carry += all;
     }
+    // ready for the next call
+    if (tid < kFinishLanes) hdr->finish[tid].value = 0u;
+    if (tid == 0) hdr->finish_top.value = 0u;
 }
 
-// Section 5.2 decoder.  values_avail = number of stored elements that may be
-// read; anything the masks ask for beyond it decodes as zero.
+// Section 5.2 decoder.  Every wave works on its own: it expands LOADS loads'
+// worth of output (LOADS x 1 KB), kStageLoads loads at a time.  For each such
+// step it knows from the pre-pass where the step's stored elements begin and
+// end, stages them in its LDS slice with aligned 16-byte loads (never past
+// values_avail elements: anything the masks ask for beyond that decodes as
+// zero), and every lane rebuilds 16 bytes of output per load from "bit ? next
+// stored element : 0".  Slots whose bit is clear read a valid dummy address and
+// select zero.
 template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
-    const unsigned* __restrict__ tile_local, const unsigned* __restrict__ chunk_total,
-    const unsigned long long* __restrict__ chunk_prefix, size_t num_groups) {
+    const unsigned* __restrict__ unit_end, const unsigned long long* __restrict__ chunk_prefix,
+    size_t num_groups) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
-    constexpr int MPT = G::kMasksPerThread;
-    constexpr int kStepGroups = kStageLoads * G::kGroupsPerLoad;  // masks per wave staging step
+    constexpr int kStepMasks = kStageLoads * G::kGroupsPerLoad;   // 32 | 64 masks per step
+    constexpr int kStepUnits = kStepMasks / kUnitMasks;           // 1 | 2
+    constexpr int kSteps = G::kStageSteps;
+    static_assert(kChunkMasks % (LOADS * G::kGroupsPerLoad) == 0, "a wave's masks lie in one chunk");
 
     __shared__ __align__(16) unsigned char s_stage[kWaves][G::kWaveStageBytes];
-    __shared__ unsigned s_mask[G::kTileGroups];
-    __shared__ unsigned s_group_offset[G::kTileGroups + 1];  // last entry = tile total
-    __shared__ unsigned s_wave_total[kWaves];
-    __shared__ unsigned long long s_chunk_prefix;
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
-    const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
-    // stored elements in the chunks before this tile's chunk: from the pre-pass
-    // totals (summed here by wave 0) or, for very large tensors, ready-made
-    const unsigned chunk = tile / (kChunkMasks / G::kTileGroups);
-    if (wave == 0) {
-        unsigned long long before = 0;
-        if (chunk_prefix != nullptr) {
-            before = chunk_prefix[chunk];
-        } else {
-            // 256 totals per round (16 bytes per lane), two rounds in flight
-            unsigned long long part = 0;
-            const uint4* totals = reinterpret_cast<const uint4*>(chunk_total);  // 256-byte aligned
-#pragma unroll 1
-            for (unsigned c0 = 0; c0 < chunk; c0 += 8 * kWaveSize) {
-                const unsigned ca = c0 + 4 * lane, cb = ca + 4 * kWaveSize;
-                uint4 va = make_uint4(0u, 0u, 0u, 0u), vb = va;
-                if (ca < chunk) va = totals[ca / 4];
-                if (cb < chunk) vb = totals[cb / 4];
-                part += (ca + 0 < chunk ? va.x : 0u) + (ca + 1 < chunk ? va.y : 0u);
-                part += (ca + 2 < chunk ? va.z : 0u) + (ca + 3 < chunk ? va.w : 0u);
-                part += (cb + 0 < chunk ? vb.x : 0u) + (cb + 1 < chunk ? vb.y : 0u);
-                part += (cb + 2 < chunk ? vb.z : 0u) + (cb + 3 < chunk ? vb.w : 0u);
-            }
-            before = wave_sum(part);
-        }
-        if (lane == 0) s_chunk_prefix = before;
-    }
-
-    // ---- MPT consecutive masks per thread: popcount, exclusive scan over the tile
-    unsigned m[MPT];
-    unsigned cnt = 0;
+    const size_t wave_elem0 =
+        (static_cast<size_t>(tile) * kWaves + wave) * (static_cast<size_t>(LOADS) * kWaveSize * E);
+    if (wave_elem0 >= n) return;                  // nothing of the tensor in this wave's part
+    const size_t wave_group0 = wave_elem0 / 32;
+    const size_t chunk = wave_group0 / kChunkMasks;
     const unsigned tail = static_cast<unsigned>(n % 32);
+
+    // ---- everything the steps need from memory, requested up front
+    const unsigned long long before_chunk = chunk_prefix[chunk];
+    unsigned m[kSteps], step_begin[kSteps], step_end[kSteps];
 #pragma unroll
-    for (int k = 0; k < MPT; ++k) {
-        const int gi = tid * MPT + k;
-        const size_t g = static_cast<size_t>(tile) * G::kTileGroups + gi;
-        m[k] = 0;
-        if (gi < G::kTileGroups && g < num_groups) {
-            m[k] = masks[g];
-            if (g == num_groups - 1 && tail != 0) m[k] &= (1u << tail) - 1u;  // bits past n never count
+    for (int h = 0; h < kSteps; ++h) {
+        const size_t g = wave_group0 + static_cast<size_t>(h) * kStepMasks + lane;
+        m[h] = 0;
+        if (lane < kStepMasks && g < num_groups) {
+            m[h] = masks[g];
+            if (g == num_groups - 1 && tail != 0) m[h] &= (1u << tail) - 1u;   // bits past n never count
         }
-        cnt += __popc(m[k]);
-    }
-    unsigned incl = cnt;
-#pragma unroll
-    for (int off = 1; off < kWaveSize; off <<= 1) {
-        const unsigned t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
-    if (lane == kWaveSize - 1) s_wave_total[wave] = incl;
-    __syncthreads();
-    unsigned wave_offset = 0, tile_total = 0;
-#pragma unroll
-    for (int v = 0; v < kWaves; ++v) {
-        const unsigned t = uniform(s_wave_total[v]);
-        if (v < wave) wave_offset += t;
-        tile_total += t;
-    }
-    {
-        unsigned off = wave_offset + incl - cnt;
-#pragma unroll
-        for (int k = 0; k < MPT; ++k) {
-            const int gi = tid * MPT + k;
-            if (gi < G::kTileGroups) {
-                s_mask[gi] = m[k];
-                s_group_offset[gi] = off;
-            }
-            off += __popc(m[k]);
-        }
-        if (tid == 0) s_group_offset[G::kTileGroups] = tile_total;
+        const size_t u = wave_group0 / kUnitMasks + static_cast<size_t>(h) * kStepUnits;
+        step_begin[h] = u % kChunkUnits != 0 ? unit_end[u - 1] : 0u;
+        step_end[h] = unit_end[u + kStepUnits - 1];
     }
 
-    __syncthreads();
-    const unsigned long long exclusive = uniform(s_chunk_prefix) + uniform(tile_local[tile]);
-    const bool full_tile = ALIGNED && tile_elem0 + G::kTileElems <= n;
-
-    // ---- expand (section 5.2: payload words or zeros muxed into place).  Each
-    //      wave stages the stored elements of kStageLoads loads' worth of output
-    //      in its LDS slice, then every lane rebuilds 16 bytes per load.  Slots
-    //      whose bit is clear read a valid dummy address and select zero.
+    const bool full_wave = ALIGNED && wave_elem0 + static_cast<size_t>(LOADS) * kWaveSize * E <= n;
     unsigned char* stage = s_stage[wave];
 #pragma unroll
-    for (int h = 0; h < G::kStageSteps; ++h) {
-        const int g0 = (wave * LOADS + h * kStageLoads) * G::kGroupsPerLoad;
-        const unsigned first_rank = uniform(s_group_offset[g0]);
-        const unsigned step_total = uniform(s_group_offset[g0 + kStepGroups]) - first_rank;
-        const unsigned long long step_begin = exclusive + first_rank;
-        const unsigned char* src = values + step_begin * W;  // wave-uniform
+    for (int h = 0; h < kSteps; ++h) {
+        const unsigned step_total = step_end[h] - step_begin[h];
+        const unsigned long long first = before_chunk + step_begin[h];
+        const unsigned char* src = values + first * W;  // wave-uniform
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
-        unsigned long long readable = values_avail > step_begin ? values_avail - step_begin : 0ull;
+        unsigned long long readable = values_avail > first ? values_avail - first : 0ull;
         if (readable > step_total) readable = step_total;
         wave_copy_in<W>(stage, src - shift, shift, shift + step_total * W,
                         shift + static_cast<unsigned>(readable) * W, lane);
+        // stored elements of the step before each of its masks (lane i holds mask i)
+        const unsigned cnt = __popc(m[h]);
+        unsigned incl = cnt;
+#pragma unroll
+        for (int off = 1; off < kStepMasks; off <<= 1) {
+            const unsigned t = __shfl_up(incl, off);
+            if (lane >= off) incl += t;
+        }
+        const unsigned before_mask = incl - cnt;
         wave_lds_sync();
 #pragma unroll
         for (int jj = 0; jj < kStageLoads; ++jj) {
-            const int seg = wave * LOADS + h * kStageLoads + jj;
-            const size_t e0 = tile_elem0 + (static_cast<size_t>(seg) * kWaveSize + lane) * E;
-            const int gi = seg * G::kGroupsPerLoad + lane / LPG;
+            const size_t e0 =
+                wave_elem0 + (static_cast<size_t>(h * kStageLoads + jj) * kWaveSize + lane) * E;
+            const int gl = jj * G::kGroupsPerLoad + lane / LPG;     // the lane's mask within the step
+            const unsigned gm = __shfl(m[h], gl);
             const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
-            const unsigned gm = s_mask[gi];
-            unsigned a = shift + W * (s_group_offset[gi] - first_rank + __popc(gm & ((1u << bit0) - 1u)));
+            unsigned at = shift + W * (__shfl(before_mask, gl) + __popc(gm & ((1u << bit0) - 1u)));
             const unsigned field = gm >> bit0;
             unsigned d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int c = 0; c < E; ++c) {
                 const bool set = (field >> c) & 1u;
-                const unsigned at = set ? a : shift;
+                const unsigned from = set ? at : shift;
                 if (W == 4) {
-                    const unsigned v = *reinterpret_cast<const unsigned*>(stage + at);
+                    const unsigned v = *reinterpret_cast<const unsigned*>(stage + from);
                     d[c] = set ? v : 0u;
                 } else {
-                    const unsigned v = *reinterpret_cast<const unsigned short*>(stage + at);
+                    const unsigned v = *reinterpret_cast<const unsigned short*>(stage + from);
                     d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
                 }
-                a += set ? W : 0;
+                at += set ? W : 0;
             }
-            if (full_tile) {
-                store16_stream(out + e0 * W, make_uint4(d[0], d[1], d[2], d[3]));
-            } else if (ALIGNED && e0 + E <= n) {
+            if (full_wave || (ALIGNED && e0 + E <= n)) {
                 store16_stream(out + e0 * W, make_uint4(d[0], d[1], d[2], d[3]));
             } else {
 #pragma unroll
@@ -982,7 +1007,6 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
 // itself.  A poll is one memory round trip (about a microsecond).
 constexpr unsigned kDefaultPatience = 2000;
 std::atomic<unsigned> g_patience{kDefaultPatience};
-std::atomic<size_t> g_inline_chunks{kInlineChunks};
 
 // Tile size of the encoder.  Each tile costs a fixed few nanoseconds of
 // chip-wide time (workgroup launch plus the scan's state traffic), so large
@@ -1012,22 +1036,23 @@ inline int choose_decoder_loads(size_t n, int w, bool aligned) {
 }
 
 template <int W, int LOADS, bool ALIGNED>
-void launch_compress_as(dim3 grid, hipStream_t stream, const unsigned char* in, size_t n,
-                        unsigned* masks, unsigned char* values, ScanState st,
-                        unsigned long long* d_bytes, unsigned tiles, size_t groups) {
-    hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream, in, n,
-                       masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles, groups,
-                       g_patience.load(std::memory_order_relaxed), scan_state_bytes(tiles));
+void launch_compress_as(hipStream_t stream, const unsigned char* in, size_t n, unsigned* masks,
+                        unsigned char* values, ScanState st, unsigned long long* d_bytes,
+                        unsigned tiles, size_t groups) {
+    const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
+                           groups, g_patience.load(std::memory_order_relaxed),
+                           scan_state_bytes(tiles)};
+    hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED>), dim3(tiles), dim3(kThreads), 0, stream,
+                       args);
 }
 
 template <int W, int LOADS, bool ALIGNED>
 void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
-                          unsigned char* out, const unsigned* tile_local,
-                          const unsigned* chunk_total, const unsigned long long* chunk_prefix,
-                          size_t groups) {
+                          unsigned char* out, const unsigned* unit_end,
+                          const unsigned long long* chunk_prefix, size_t groups) {
     hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, tile_local, chunk_total, chunk_prefix, groups);
+                       masks, values, avail, n, out, unit_end, chunk_prefix, groups);
 }
 
 // Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
@@ -1054,9 +1079,6 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
     if (!aligned) {
         if (w == 4) launch_decompress_as<4, kMinLoads, false>(args...);
         else launch_decompress_as<2, kMinLoads, false>(args...);
-    } else if (loads == 16) {
-        if (w == 4) launch_decompress_as<4, 16, true>(args...);
-        else launch_decompress_as<2, 16, true>(args...);
     } else if (loads == 8) {
         if (w == 4) launch_decompress_as<4, 8, true>(args...);
         else launch_decompress_as<2, 8, true>(args...);
@@ -1096,7 +1118,7 @@ size_t zvc_workspace_bytes(size_t n, int w) {
     if (w != 2 && w != 4) return 0;
     const size_t tiles = tiles_for(n, w, kMinLoads);
     return kHeaderBytes + scan_state_bytes(tiles) +
-           decoder_area_bytes(tiles, div_up(div_up(n, 32), kChunkMasks));
+           decoder_area_bytes(div_up(div_up(n, 32), kChunkMasks));
 }
 
 zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w) {
@@ -1122,12 +1144,16 @@ zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream) {
     return launch_reset(d_ws, (ws - kHeaderBytes) / 8 * 8, stream);
 }
 
+#ifdef ZVC_TRACE
+// d_words: 8 * tiles device words, or null to switch tracing off.
+zvc_status zvc_trace_set(void* d_words) {
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_trace_words), &d_words, sizeof(d_words)) == hipSuccess
+               ? ZVC_OK : ZVC_E_HIP;
+}
+#endif
+
 void zvc_set_lookback_patience(unsigned polls) {
     g_patience.store(polls, std::memory_order_relaxed);
-}
-
-void zvc_set_decoder_inline_chunks(size_t chunks) {
-    g_inline_chunks.store(chunks, std::memory_order_relaxed);
 }
 
 zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count) {
@@ -1191,8 +1217,8 @@ zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t o
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
     unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    launch_compress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, in, n, masks, values,
-                    scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups);
+    launch_compress(w, loads, al, stream, in, n, masks, values, scan_state(d_ws, tiles), out_bytes,
+                    static_cast<unsigned>(tiles), groups);
     return hip_ok(hipGetLastError());
 }
 
@@ -1211,30 +1237,22 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(groups, kChunkMasks);
+    if (chunks > 0xFFFFFFFFull) return ZVC_E_ARG;
     // pre-pass arrays live after the encoder's scan state and need no reset
     unsigned char* area = static_cast<unsigned char*>(d_ws) + kHeaderBytes +
                           scan_state_bytes(tiles_for(n, w, kMinLoads));
     unsigned long long* chunk_prefix = reinterpret_cast<unsigned long long*>(area);
     unsigned* chunk_total = reinterpret_cast<unsigned*>(area + pad256(8 * chunks));
-    unsigned* tile_local = reinterpret_cast<unsigned*>(area + pad256(8 * chunks) + pad256(4 * chunks));
+    unsigned* unit_end = reinterpret_cast<unsigned*>(area + pad256(8 * chunks) + pad256(4 * chunks));
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
-    const unsigned tile_masks = static_cast<unsigned>(kThreads * 16 * loads / w / 32);
     hipLaunchKernelGGL(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), 0,
-                       stream, masks, groups, static_cast<unsigned>(n % 32), tile_masks,
-                       static_cast<unsigned>(tiles), tile_local, chunk_total);
+                       stream, masks, groups, static_cast<unsigned>(n % 32), unit_end, chunk_total,
+                       chunk_prefix, static_cast<WsHeader*>(d_ws), static_cast<unsigned>(chunks));
     if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
-    const unsigned long long* ready_prefix = nullptr;
-    if (chunks > g_inline_chunks.load(std::memory_order_relaxed)) {
-        hipLaunchKernelGGL(chunk_scan_kernel, dim3(1), dim3(kThreads), 0, stream, chunk_total,
-                           chunk_prefix, chunks);
-        if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
-        ready_prefix = chunk_prefix;
-    }
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
     launch_decompress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values,
-                      avail, n, static_cast<unsigned char*>(d_out), tile_local, chunk_total,
-                      ready_prefix, groups);
+                      avail, n, static_cast<unsigned char*>(d_out), unit_end, chunk_prefix, groups);
     return hip_ok(hipGetLastError());
 }
 

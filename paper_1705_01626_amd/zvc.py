@@ -25,8 +25,7 @@ STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_W
 EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
-           "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
-           "zvc_set_decoder_inline_chunks")
+           "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count")
 
 _lib = None
 
@@ -72,8 +71,6 @@ def load() -> ctypes.CDLL:
     lib.zvc_prefetch.argtypes = [vp, u64, sz, ci, vp, sz, vp, vp, sz, vp, vp]
     lib.zvc_set_lookback_patience.restype = None
     lib.zvc_set_lookback_patience.argtypes = [ctypes.c_uint]
-    lib.zvc_set_decoder_inline_chunks.restype = None
-    lib.zvc_set_decoder_inline_chunks.argtypes = [sz]
     lib.zvc_workspace_self_help_count.restype = ci
     lib.zvc_workspace_self_help_count.argtypes = [vp, vp]
     _lib = lib
@@ -120,10 +117,6 @@ def zvc_check_stream(h_comp: torch.Tensor, nbytes: int, n: int, w: int) -> int:
 
 def zvc_set_lookback_patience(polls: int) -> None:
     load().zvc_set_lookback_patience(int(polls))
-
-
-def zvc_set_decoder_inline_chunks(chunks: int) -> None:
-    load().zvc_set_decoder_inline_chunks(int(chunks))
 
 
 def zvc_workspace_self_help_count(ws: torch.Tensor) -> int:

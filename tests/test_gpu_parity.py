@@ -246,13 +246,13 @@ def test_no_self_help_in_normal_runs(oracle):
     assert torch.equal(out, x)
 
 
-def test_decoder_with_prefixed_chunk_totals(oracle):
-    """The path for tensors past 2^31 elements (chunk totals prefixed by a
-    one-workgroup kernel), forced on tensors of ordinary size."""
-    try:
-        zvc.zvc_set_decoder_inline_chunks(0)
-        for w, n in ((4, 3000001), (2, 40000003), (4, 1000)):
-            x = random_tensor(n, w, 0.33, seed=w * n)
-            assert_parity(x, oracle, "prefixed chunk totals")
-    finally:
-        zvc.zvc_set_decoder_inline_chunks(4096)
+def test_decoder_many_chunks_and_reuse(oracle):
+    """The decoder's pre-pass: one workgroup per 4096 masks, the last one to
+    finish prefixes the chunk totals and resets its counter.  Sizes from one
+    chunk to several hundred, the same workspace reused back to back."""
+    w = 4
+    n_max = 4096 * 32 * 300 + 12345
+    ws = zvc.new_workspace(n_max, w, DEV)
+    for n in (4096 * 32, 4096 * 32 + 1, 4096 * 32 * 2 - 1, n_max, 4096 * 32 * 7 + 31, 1000):
+        x = random_tensor(n, w, 0.41, seed=n)
+        assert_parity(x, oracle, "pre-pass chunks n=%d" % n, ws=ws)
