@@ -44,6 +44,9 @@ constexpr int kStageLoads = 4;                // 16-byte loads a wave stages thr
 constexpr int kBlockTiles = 64;               // one running prefix is published per 64 tiles
 constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
 
+#ifndef ZVC_ENC_STAGE_LOADS
+#define ZVC_ENC_STAGE_LOADS 4
+#endif
 // A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
 template <int W, int LOADS>
 struct Geometry {
@@ -62,6 +65,10 @@ struct Geometry {
     // (16 bytes so the slice can mirror the destination's alignment)
     static constexpr int kWaveStageBytes = kStageLoads * kWaveSize * 16 + 16;
     static_assert(LOADS % kStageLoads == 0, "tile is staged in whole steps");
+    // loads the encoder stages at a time (a build-time knob; 4 and 8 measure alike, 16 costs occupancy)
+    static constexpr int kEncStageLoads = LOADS >= ZVC_ENC_STAGE_LOADS ? ZVC_ENC_STAGE_LOADS : kStageLoads;
+    static constexpr int kEncStageSteps = LOADS / kEncStageLoads;
+    static constexpr int kEncWaveStageBytes = kEncStageLoads * kWaveSize * 16 + 16;
 };
 
 // Workspace header.  Lives at the start of the caller's workspace.
@@ -74,11 +81,12 @@ struct WsHeader {
     unsigned long long pad[28];
     // Arrival counters, shared by the encoder and the decoder's pre-pass (calls
     // on one workspace do not overlap).  Encoder: tile t counts itself finished
-    // in finish[t % 64] once it has read all the scan state it needs; the tile
-    // that completes a lane bumps finish_top; the tile that completes finish_top
-    // zeroes the scan state and these counters, so the next call needs no reset
-    // kernel.  One counter per 128-byte line keeps the atomics on one address
-    // T/64 apart.
+    // in finish[t % 64] once it has read all the scan state it needs; the last
+    // tile waits until all have, then zeroes the scan state and these counters,
+    // so the next call needs no reset kernel.  Pre-pass: the workgroup that
+    // completes a counter bumps finish_top, the one that completes finish_top is
+    // the last.  One counter per 128-byte line keeps the atomics on one address
+    // (about 11 ns each) far apart in time.
     struct alignas(128) Line { unsigned value; } finish[kFinishLanes], finish_top;
 };
 static_assert(sizeof(WsHeader) == kHeaderBytes, "header size");
@@ -422,35 +430,33 @@ __device__ inline unsigned long long tile_exclusive_prefix(unsigned* counts,
     return exclusive;
 }
 
-// Encoder clean-up, see WsHeader::finish.  finish_ticket() is called by lane 0
+// Encoder clean-up, see WsHeader::finish.  finish_arrive() is called by lane 0
 // of the scan wave once the tile has read all the scan state it needs and its
 // own words have been written (the s_waitcnt makes the write-through stores
 // complete before the counter moves, so no late store can land after the
-// clean-up).  finish_tile() is called by the same wave at the end of the tile.
-__device__ inline unsigned finish_ticket(WsHeader* hdr, unsigned tile) {
+// clean-up).  The atomic returns nothing, so no wave ever waits for it.
+__device__ inline void finish_arrive(WsHeader* hdr, unsigned tile) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    return atomicAdd(&hdr->finish[tile % kFinishLanes].value, 1u);
+    __hip_atomic_fetch_add(&hdr->finish[tile % kFinishLanes].value, 1u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ inline void finish_tile(WsHeader* hdr, unsigned* counts, unsigned tile,
-                                   unsigned num_tiles, unsigned ticket, int lane,
+// Called by the scan wave of the last tile at its end: waits until every tile
+// of the call has arrived (none of them waits for this one, and the last tile
+// is dispatched last, so the wait is short), then zeroes the scan state and the
+// counters for the next call.
+__device__ inline void finish_call(WsHeader* hdr, unsigned* counts, unsigned num_tiles, int lane,
                                    size_t state_bytes) {
-    unsigned last = 0;
-    if (lane == 0) {
-        const unsigned slot = tile % kFinishLanes;
-        const unsigned quota = num_tiles / kFinishLanes + (slot < num_tiles % kFinishLanes ? 1u : 0u);
-        if (ticket == quota - 1) {
-            const unsigned slots_used = num_tiles < kFinishLanes ? num_tiles : kFinishLanes;
-            last = atomicAdd(&hdr->finish_top.value, 1u) == slots_used - 1 ? 1u : 0u;
-        }
+    while (true) {
+        const unsigned long long arrived = wave_sum(static_cast<unsigned long long>(
+            __hip_atomic_load(&hdr->finish[lane].value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+        if (arrived == num_tiles) break;
+        __builtin_amdgcn_s_sleep(kPollSleep);
     }
-    if (__shfl(last, 0) == 0u) return;
-    // every tile of this call has finished with the scan state: zero it for the next call
     uint4* p = reinterpret_cast<uint4*>(counts);   // counts then prefixes, 256-byte aligned
     const size_t chunks = state_bytes / 16;
     for (size_t i = lane; i < chunks; i += kWaveSize) p[i] = make_uint4(0u, 0u, 0u, 0u);
     hdr->finish[lane].value = 0u;
-    if (lane == 0) hdr->finish_top.value = 0u;
 }
 
 // Count of non-zero elements of input tile q, by one wave (scan self-help).
@@ -536,7 +542,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
 
-    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kWaveStageBytes];
+    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kEncWaveStageBytes];
     __shared__ unsigned s_wave_total[kWaves];
     __shared__ unsigned long long s_prefix;
 
@@ -606,7 +612,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     }
 
     // ---- device-wide exclusive scan, wave 0
-    unsigned ticket = 0;
     if (wave == 0) {
         const CountInputTile<W, LOADS, ALIGNED> count_tile{a.in, a.n};
         const unsigned long long ex = tile_exclusive_prefix(a.counts, a.prefixes, tile, tile_total,
@@ -616,25 +621,24 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     }
     lds_barrier();
     const unsigned long long exclusive = uniform(s_prefix);
-    // after the barrier, so that only this wave waits for its state stores to complete;
-    // the counter's answer comes back while the wave does its share of the compaction
-    if (wave == 0 && lane == 0) ticket = finish_ticket(a.hdr, tile);
+    // after the barrier, so that only this wave waits for its state stores to complete
+    if (wave == 0 && lane == 0) finish_arrive(a.hdr, tile);
 
     // ---- compaction (section 5.2: shift non-zeros to their packed slots).
-    //      Each wave stages kStageLoads loads at a time in its own LDS slice in
+    //      Each wave stages kEncStageLoads loads at a time in its own LDS slice in
     //      packed order, then copies the run out.  LDS byte p of the slice
     //      corresponds to global byte (dst - shift) + p, so 16-byte chunks are
     //      aligned on both sides.
     unsigned char* stage = s_stage[wave];
 #pragma unroll
-    for (int h = 0; h < G::kStageSteps; ++h) {
-        const unsigned first_rank = run[h * kStageLoads];
-        const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
+    for (int h = 0; h < G::kEncStageSteps; ++h) {
+        const unsigned first_rank = run[h * G::kEncStageLoads];
+        const unsigned step_total = run[(h + 1) * G::kEncStageLoads] - first_rank;
         unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W;  // wave-uniform
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
 #pragma unroll
-        for (int jj = 0; jj < kStageLoads; ++jj) {
-            const int j = h * kStageLoads + jj;
+        for (int jj = 0; jj < G::kEncStageLoads; ++jj) {
+            const int j = h * G::kEncStageLoads + jj;
             unsigned char* at = stage + (shift + W * (run[j] - first_rank)) +
                                 W * ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
 #pragma unroll
@@ -661,7 +665,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     if (tile == a.num_tiles - 1 && tid == 0)
         *a.d_bytes = 4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
 
-    if (wave == 0) finish_tile(a.hdr, a.counts, tile, a.num_tiles, ticket, lane, a.state_bytes);
+    if (tile == a.num_tiles - 1 && wave == 0)
+        finish_call(a.hdr, a.counts, a.num_tiles, lane, a.state_bytes);
 }
 
 // Decoder pre-pass (section 5.2: the popcount of a mask span is the number of
