@@ -73,9 +73,7 @@ struct Geometry {
 
 // Workspace header.  Lives at the start of the caller's workspace.
 struct WsHeader {
-    unsigned int done;             // finished workgroups (count-only pass)
-    unsigned int pad0;
-    unsigned long long nnz;        // accumulator of the count-only pass
+    unsigned long long pad0[2];
     unsigned long long size_word;  // compressed size for zvc_offload's read-back
     unsigned long long helped;     // predecessor counts computed by a waiting tile (last encoder call)
     unsigned long long pad[28];
@@ -85,9 +83,10 @@ struct WsHeader {
     // tile waits until all have, then zeroes the scan state and these counters,
     // so the next call needs no reset kernel.  Pre-pass: the workgroup that
     // completes a counter bumps finish_top, the one that completes finish_top is
-    // the last.  One counter per 128-byte line keeps the atomics on one address
-    // (about 11 ns each) far apart in time.
-    struct alignas(128) Line { unsigned value; } finish[kFinishLanes], finish_top;
+    // the last.  Count-only pass: the same, with `sum` collecting the counts.
+    // One counter per 128-byte line keeps the atomics on one address (about
+    // 11 ns each) far apart in time.
+    struct alignas(128) Line { unsigned value; unsigned pad; unsigned long long sum; } finish[kFinishLanes], finish_top;
 };
 static_assert(sizeof(WsHeader) == kHeaderBytes, "header size");
 
@@ -589,6 +588,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         if (j == 0) ZVC_TRACE_POINT(tile, 1);
     }
     ZVC_TRACE_POINT(tile, 2);
+    // The compaction tests the elements again.  Hide from the compiler that it
+    // has compared these registers before: it would keep all the ballots for
+    // later, which costs more (lane-spills) than the second compare.
+#pragma unroll
+    for (int j = 0; j < LOADS; ++j)
+        asm volatile("" : "+v"(cur[j].x), "+v"(cur[j].y), "+v"(cur[j].z), "+v"(cur[j].w));
 #pragma unroll
     for (int q = 0; q < G::kMaskRegs; ++q) {
         const int j = q * LPG + lane_in_group;  // the load whose mask this lane kept
@@ -932,38 +937,69 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     }
 }
 
-// Count-only pass (section 5.4's size, without producing the stream).
+// Count-only pass (section 5.4's size, without producing the stream).  One
+// workgroup per 32 KB of input, all of a thread's loads in flight together.
+// A workgroup adds (1 << 40) + its count to one of 64 accumulators with a single
+// atomic: the low 40 bits collect kept elements, the high bits count arrivals.
+// The workgroup that completes an accumulator bumps finish_top; the one that
+// completes finish_top adds the 64 sums up, reports, and leaves the accumulators
+// at zero for the next call.
+constexpr int kCountLoads = 8;
+constexpr int kCountShift = 40;
+
 template <int W, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void count_kernel(const unsigned char* __restrict__ in,
                                                          size_t n, WsHeader* hdr,
                                                          unsigned long long* d_bytes,
-                                                         size_t num_groups) {
+                                                         size_t num_groups, unsigned num_tiles) {
     constexpr int E = 16 / W;
     __shared__ unsigned long long s_wave[kWaves];
-    const size_t chunks = div_up(n, E);
-    unsigned long long count = 0;
-    for (size_t q = blockIdx.x * static_cast<size_t>(kThreads) + threadIdx.x; q < chunks;
-         q += static_cast<size_t>(gridDim.x) * kThreads) {
-        const uint4 v = load_chunk<W, ALIGNED>(in, q * E, n);
-        count += __popc(presence_bits<W>(v));
+    __shared__ unsigned s_last;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = tid / kWaveSize;
+    const unsigned tile = blockIdx.x;
+    const size_t q0 = static_cast<size_t>(tile) * (kThreads * kCountLoads) + tid;
+    uint4 v[kCountLoads];
+    if (ALIGNED && (q0 - tid + kThreads * kCountLoads) * E <= n) {
+#pragma unroll
+        for (int j = 0; j < kCountLoads; ++j)
+            v[j] = load16_stream(in + (q0 + static_cast<size_t>(j) * kThreads) * 16);
+    } else {
+#pragma unroll
+        for (int j = 0; j < kCountLoads; ++j)
+            v[j] = load_chunk<W, ALIGNED>(in, (q0 + static_cast<size_t>(j) * kThreads) * E, n);
     }
+    unsigned long long count = 0;
+#pragma unroll
+    for (int j = 0; j < kCountLoads; ++j) count += __popc(presence_bits<W>(v[j]));
     count = wave_sum(count);
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x / kWaveSize;
     if (lane == 0) s_wave[wave] = count;
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         unsigned long long block_total = 0;
-        for (int v = 0; v < kWaves; ++v) block_total += s_wave[v];
-        const unsigned long long before = atomicAdd(&hdr->nnz, block_total);
-        asm volatile("" : : "v"(before) : "memory");   // performed before the counter moves
-        const unsigned finished = atomicAdd(&hdr->done, 1u);
-        if (finished == gridDim.x - 1) {
-            // last workgroup: report, and leave the accumulators at zero for the next call
-            const unsigned long long total = atomicExch(&hdr->nnz, 0ull);
-            *d_bytes = 4ull * num_groups + static_cast<unsigned long long>(W) * total;
-            hdr->done = 0u;
+        for (int k = 0; k < kWaves; ++k) block_total += s_wave[k];
+        const unsigned slot = tile % kFinishLanes;
+        const unsigned quota = num_tiles / kFinishLanes + (slot < num_tiles % kFinishLanes ? 1u : 0u);
+        const unsigned long long old =
+            atomicAdd(&hdr->finish[slot].sum, (1ull << kCountShift) + block_total);
+        unsigned last = 0;
+        if ((old >> kCountShift) == quota - 1) {
+            const unsigned slots_used = num_tiles < kFinishLanes ? num_tiles : kFinishLanes;
+            last = atomicAdd(&hdr->finish_top.value, 1u) == slots_used - 1 ? 1u : 0u;
         }
+        s_last = last;
+    }
+    __syncthreads();
+    if (s_last == 0u || wave != 0) return;
+    const unsigned long long part =
+        __hip_atomic_load(&hdr->finish[lane].sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) &
+        ((1ull << kCountShift) - 1);
+    const unsigned long long total = wave_sum(part);
+    hdr->finish[lane].sum = 0ull;
+    if (lane == 0) {
+        *d_bytes = 4ull * num_groups + static_cast<unsigned long long>(W) * total;
+        hdr->finish_top.value = 0u;
     }
 }
 
@@ -1181,18 +1217,17 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
     WsHeader* hdr = static_cast<WsHeader*>(d_ws);   // accumulators are zero between calls
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     const size_t groups = div_up(n, 32);
-    const size_t chunks = div_up(n * static_cast<size_t>(w), 16);
-    // one same-address atomic per block: keep the block count low
-    size_t blocks = div_up(chunks, static_cast<size_t>(kThreads) * 8);
-    if (blocks > 1024) blocks = 1024;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const size_t tiles = div_up(n * static_cast<size_t>(w), static_cast<size_t>(kThreads) * 16 * kCountLoads);
+    if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
+    const dim3 grid(static_cast<unsigned>(tiles)), block(kThreads);
+    const unsigned nt = static_cast<unsigned>(tiles);
     const bool al = aligned_to(d_in, 16);
     if (w == 4) {
-        if (al) hipLaunchKernelGGL((count_kernel<4, true>), grid, block, 0, stream, in, n, hdr, out, groups);
-        else hipLaunchKernelGGL((count_kernel<4, false>), grid, block, 0, stream, in, n, hdr, out, groups);
+        if (al) hipLaunchKernelGGL((count_kernel<4, true>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
+        else hipLaunchKernelGGL((count_kernel<4, false>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
     } else {
-        if (al) hipLaunchKernelGGL((count_kernel<2, true>), grid, block, 0, stream, in, n, hdr, out, groups);
-        else hipLaunchKernelGGL((count_kernel<2, false>), grid, block, 0, stream, in, n, hdr, out, groups);
+        if (al) hipLaunchKernelGGL((count_kernel<2, true>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
+        else hipLaunchKernelGGL((count_kernel<2, false>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
     }
     return hip_ok(hipGetLastError());
 }
