@@ -1052,8 +1052,7 @@ std::atomic<unsigned> g_patience{kDefaultPatience};
 // Tile size of the encoder.  Each tile costs a fixed few nanoseconds of
 // chip-wide time (workgroup launch plus the scan's state traffic), so large
 // tensors use 64 KB tiles; smaller tensors use smaller tiles so that every CU
-// still gets several.  The decoder has no scan in its main kernel and does
-// best with mid-sized tiles.
+// still gets several.
 #ifndef ZVC_FORCE_LOADS
 #define ZVC_FORCE_LOADS 0
 #endif
@@ -1070,10 +1069,11 @@ inline int choose_loads(size_t n, int w, bool aligned) {
     return bytes >= kLargeTensorBytes ? 16 : bytes >= kMediumTensorBytes ? 8 : 4;
 }
 
-inline int choose_decoder_loads(size_t n, int w, bool aligned) {
-    if (!aligned) return kMinLoads;
-    if (ZVC_FORCE_DECODER_LOADS != 0) return ZVC_FORCE_DECODER_LOADS;
-    return n * static_cast<size_t>(w) >= kLargeTensorBytes ? 8 : 4;
+// The decoder's waves are independent, so its tile only sets how many staging
+// steps a wave does one after the other: one step (16 KB tiles) measures best
+// at every size.
+inline int choose_decoder_loads(size_t, int, bool) {
+    return ZVC_FORCE_DECODER_LOADS != 0 ? ZVC_FORCE_DECODER_LOADS : kMinLoads;
 }
 
 template <int W, int LOADS, bool ALIGNED>
@@ -1120,6 +1120,9 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
     if (!aligned) {
         if (w == 4) launch_decompress_as<4, kMinLoads, false>(args...);
         else launch_decompress_as<2, kMinLoads, false>(args...);
+    } else if (loads == 16) {
+        if (w == 4) launch_decompress_as<4, 16, true>(args...);
+        else launch_decompress_as<2, 16, true>(args...);
     } else if (loads == 8) {
         if (w == 4) launch_decompress_as<4, 8, true>(args...);
         else launch_decompress_as<2, 8, true>(args...);
