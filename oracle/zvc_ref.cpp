@@ -23,6 +23,14 @@
 //   2. bit order: bit 0 (least significant) is the first element of the group.
 //   3. "zero" is the all-zero bit pattern; -0.0, NaN and denormals are kept.
 //   4. a ragged tail group has zero bits past n and stores nothing for them.
+//   5. (fused ReLU + ZVC, zvc_ref_relu*) the elements are IEEE-style numbers
+//      with the sign in the top bit (fp32, fp16, bf16).  ReLU keeps an element
+//      unchanged when its sign bit is clear and it is not +0, and turns every
+//      other element into +0.  So every positive number, denormals and +inf
+//      included, is kept; -0.0 and all negative numbers become +0; a NaN is
+//      kept when its sign bit is clear and dropped when it is set (max(0, NaN)
+//      is 0 by IEEE maxNum and NaN in common frameworks: no choice matches
+//      all, this one needs no floating-point mode).
 //
 // Entry points are extern "C" so tests can bind them with ctypes.
 
@@ -154,6 +162,33 @@ uint64_t zvc_ref_count_nonzero(const void* in_, uint64_t n, int w) {
     uint64_t kept = 0;
     for (uint64_t i = 0; i < n; ++i) kept += (element_bits(in, i, w) != 0) ? 1 : 0;
     return kept;
+}
+
+// ReLU, element by element (section 4: the zeros that ZVC removes are the
+// outputs of ReLU layers; reading 5 above).  out may alias in.
+int zvc_ref_relu(const void* in_, uint64_t n, int w, void* out_) {
+    if (w != 2 && w != 4) return -1;
+    const unsigned char* in = static_cast<const unsigned char*>(in_);
+    unsigned char* out = static_cast<unsigned char*>(out_);
+    const uint32_t sign = w == 4 ? 0x80000000u : 0x8000u;
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint32_t word = element_bits(in, i, w);
+        const bool positive = (word & sign) == 0 && word != 0;
+        if (positive)
+            std::memmove(out + i * w, in + i * w, static_cast<size_t>(w));
+        else
+            std::memset(out + i * w, 0, static_cast<size_t>(w));
+    }
+    return 0;
+}
+
+// Fused ReLU + ZVC: by definition the ZVC stream of ReLU(in).  Written as
+// exactly that composition: ReLU into a temporary, then the encoder above.
+uint64_t zvc_ref_relu_compress_stream(const void* in, uint64_t n, int w, void* out) {
+    if (w != 2 && w != 4) return UINT64_MAX;
+    std::vector<unsigned char> activated(static_cast<size_t>(n) * static_cast<size_t>(w));
+    zvc_ref_relu(in, n, w, activated.data());
+    return zvc_ref_compress_stream(activated.data(), n, w, out);
 }
 
 }  // extern "C"

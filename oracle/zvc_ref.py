@@ -39,6 +39,11 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
     lib.zvc_ref_decompress_stream.argtypes = [vp, _U64, ip, vp]
     lib.zvc_ref_count_nonzero.restype = _U64
     lib.zvc_ref_count_nonzero.argtypes = [vp, _U64, ip]
+    if hasattr(lib, "zvc_ref_relu"):   # absent from mutated copies built before it existed
+        lib.zvc_ref_relu.restype = ip
+        lib.zvc_ref_relu.argtypes = [vp, _U64, ip, vp]
+        lib.zvc_ref_relu_compress_stream.restype = _U64
+        lib.zvc_ref_relu_compress_stream.argtypes = [vp, _U64, ip, vp]
     _lib_cache[path] = lib
     return lib
 
@@ -114,3 +119,26 @@ def count_nonzero(x: np.ndarray, w: int, lib=None) -> int:
     lib = lib or load()
     raw = _as_bytes(x)
     return int(lib.zvc_ref_count_nonzero(_ptr(raw), raw.size // w, w))
+
+
+def relu(x: np.ndarray, w: int, lib=None) -> np.ndarray:
+    """ReLU of the raw bytes of `x` taken as w-byte sign-magnitude floats; uint8[n * w]."""
+    lib = lib or load()
+    raw = _as_bytes(x)
+    n = raw.size // w
+    out = np.full(max(n * w, 1), 0xAB, dtype=np.uint8)
+    if lib.zvc_ref_relu(_ptr(raw), n, w, _ptr(out)) != 0:
+        raise ValueError("unsupported element width %r" % (w,))
+    return out[: n * w]
+
+
+def relu_compress_stream(x: np.ndarray, w: int, lib=None) -> np.ndarray:
+    """The [masks][values] stream of ReLU(x) (fused ReLU + ZVC)."""
+    lib = lib or load()
+    raw = _as_bytes(x)
+    n = raw.size // w
+    out = np.zeros(4 * groups(n, lib) + n * w + 1, dtype=np.uint8)
+    used = lib.zvc_ref_relu_compress_stream(_ptr(raw), n, w, _ptr(out))
+    if used == _BAD:
+        raise ValueError("unsupported element width %r" % (w,))
+    return out[:used].copy()

@@ -18,9 +18,9 @@ def _words(tokens, w):
     return np.array(out, dtype=dtype)
 
 
-def load_handbuilt():
+def load_handbuilt(filename="handbuilt_cases.txt"):
     cases, cur = [], None
-    with open(os.path.join(GOLDEN_DIR, "handbuilt_cases.txt")) as f:
+    with open(os.path.join(GOLDEN_DIR, filename)) as f:
         for line in f:
             line = line.strip()
             if not line or line.startswith("#"):
@@ -32,8 +32,8 @@ def load_handbuilt():
                 cases.append(cur)
             elif key in ("n", "w", "bytes"):
                 cur[key] = int(rest)
-            elif key == "in":
-                cur["in"] = _words(toks, cur["w"])
+            elif key in ("in", "relu"):
+                cur[key] = _words(toks, cur["w"])
             elif key == "masks":
                 cur["masks"] = _words(toks, 4)
             elif key == "values":
@@ -41,6 +41,10 @@ def load_handbuilt():
     for c in cases:
         assert c["in"].size == c["n"], c["name"]
     return cases
+
+
+def load_relu_cases():
+    return load_handbuilt("relu_cases.txt")
 
 
 def load_paper_numbers():

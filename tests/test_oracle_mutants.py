@@ -9,7 +9,8 @@ import pytest
 from oracle import build as oracle_build
 from oracle import zvc_ref
 from tests import test_oracle as pins
-from tests.golden_cases import load_handbuilt
+from tests import test_oracle_relu as relu_pins
+from tests.golden_cases import load_handbuilt, load_relu_cases
 
 MUTANTS = [
     ("msb_first_bit_order", "m |= (uint32_t{1} << b);", "m |= (uint32_t{1} << (31 - b));"),
@@ -35,6 +36,16 @@ MUTANTS = [
     ("decoder_skips_zero_fill", "std::memset(out + i * w, 0, static_cast<size_t>(w));", "(void)0;"),
     ("count_ignores_high_half", "kept += (element_bits(in, i, w) != 0) ? 1 : 0;",
      "kept += ((element_bits(in, i, w) & 0xFFFFu) != 0) ? 1 : 0;"),
+    ("relu_ignores_sign", "const bool positive = (word & sign) == 0 && word != 0;",
+     "const bool positive = word != 0;"),
+    ("relu_keeps_negatives_instead", "const bool positive = (word & sign) == 0 && word != 0;",
+     "const bool positive = (word & sign) != 0;"),
+    ("relu_halfword_sign_in_wrong_bit", "const uint32_t sign = w == 4 ? 0x80000000u : 0x8000u;",
+     "const uint32_t sign = w == 4 ? 0x80000000u : 0x4000u;"),
+    ("relu_leaves_dropped_elements_in_place", "std::memset(out + i * w, 0, static_cast<size_t>(w));\n    }\n    return 0;",
+     "(void)0;\n    }\n    return 0;"),
+    ("fused_skips_relu", "return zvc_ref_compress_stream(activated.data(), n, w, out);",
+     "return zvc_ref_compress_stream(in, n, w, out);"),
 ]
 
 
@@ -56,12 +67,19 @@ def _pin_suite(oracle):
     pins.test_layout_independence(oracle)
     pins.test_random_byte_soup_round_trip(oracle)
     pins.test_values_preserve_order(oracle)
+    for case in load_relu_cases():
+        relu_pins.test_relu_handbuilt_cases(oracle, case)
+    relu_pins.test_relu_matches_numpy_maximum_fp32(oracle)
+    relu_pins.test_relu_rule_on_every_16bit_pattern(oracle)
+    for w in (2, 4):
+        for n in (33, 4097):
+            relu_pins.test_fused_is_zvc_of_relu(oracle, n, w)
 
 
 def _bound(lib):
     ns = types.SimpleNamespace()
     for name in ("groups", "compressed_bytes", "compress", "compress_stream", "decompress",
-                 "decompress_stream", "count_nonzero"):
+                 "decompress_stream", "count_nonzero", "relu", "relu_compress_stream"):
         fn = getattr(zvc_ref, name)
         setattr(ns, name, (lambda f: lambda *a: f(*a, lib=lib))(fn))
     return ns
