@@ -64,9 +64,11 @@ def event_timed(fn, reps: int, torch) -> float:
     return start.elapsed_time(stop) / reps
 
 
-def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0):
+def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool = False):
     """The oracle as it stands, single thread, on the same bytes: whole-tensor
-    compress + decompress round trips until about `budget_s` seconds are spent."""
+    compress + decompress round trips until about `budget_s` seconds are spent.
+    With `relu` the encoder is the oracle's fused ReLU + ZVC (ReLU into a
+    temporary, then the plain encoder)."""
     import numpy as np
     from oracle import zvc_ref
     lib = zvc_ref.load()
@@ -77,13 +79,18 @@ def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0):
     reps, spent, best = 0, 0.0, None
     while reps < 1 or (spent < budget_s and reps < 50):
         t0 = time.perf_counter()
-        lib.zvc_ref_compress_stream(vp(host_bytes.ctypes.data), n, w, vp(comp.ctypes.data))
+        encode = lib.zvc_ref_relu_compress_stream if relu else lib.zvc_ref_compress_stream
+        encode(vp(host_bytes.ctypes.data), n, w, vp(comp.ctypes.data))
         lib.zvc_ref_decompress_stream(vp(comp.ctypes.data), n, w, vp(back.ctypes.data))
         dt = time.perf_counter() - t0
         spent += dt
         reps += 1
         best = dt if best is None else min(best, dt)
-    assert np.array_equal(back[: n * w], host_bytes[: n * w])
+    if relu:
+        from oracle import zvc_ref as ref
+        assert np.array_equal(back[: n * w], ref.relu(host_bytes[: n * w], w))
+    else:
+        assert np.array_equal(back[: n * w], host_bytes[: n * w])
     return {"value": round(2.0 * n * w / best / 1e9, 4), "unit": "GB/s", "cores": 1,
             "kind": "oracle",
             "sample": "whole tensor (%d bytes), %d compress+decompress round trips, best" % (n * w, reps)}
@@ -213,6 +220,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="conv1_style")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--relu", action="store_true",
+                    help="time the fused ReLU + ZVC encoder on pre-activations of the workload "
+                         "(zeros of the tensor replaced by negative values)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--counter-pass", action="store_true",
@@ -234,20 +244,27 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     x, described = make_workload(args.workload, args.seed, dev)
+    x_in = x
+    if args.relu:
+        from paper_1705_01626_amd import workloads
+        x_in = workloads.pre_activation(x.float(), args.seed + 1).to(x.dtype)
+        x = torch.relu(x_in)          # what the round trip must give back
+        described += "; pre-activations (zeros replaced by negative draws), fused ReLU + ZVC encoder"
+    encode = zvc.zvc_relu_compress if args.relu else zvc.zvc_compress
     n, w = x.numel(), x.element_size()
     ws = zvc.new_workspace(n, w, dev)
     comp = zvc.new_compressed_buffer(n, w, dev)
     d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
     out = torch.empty_like(x)
 
-    zvc.zvc_compress(x, comp, d_bytes, ws)
+    encode(x_in, comp, d_bytes, ws)
     nbytes = int(d_bytes.item())
     groups = (n + 31) // 32
     nnz = (nbytes - 4 * groups) // w
     density = nnz / n
 
     def compress():
-        zvc.zvc_compress(x, comp, d_bytes, ws)
+        encode(x_in, comp, d_bytes, ws)
 
     def decompress():
         zvc.zvc_decompress(comp, nbytes, out, ws)
@@ -311,7 +328,8 @@ def main() -> int:
         "config": {"workload": args.workload, "tensor": described, "elements": n,
                    "element_bytes": w, "uncompressed_bytes": uncompressed,
                    "compressed_bytes": nbytes, "density": round(density, 6),
-                   "compression_ratio": round(uncompressed / nbytes, 4), "seed": args.seed},
+                   "compression_ratio": round(uncompressed / nbytes, 4), "seed": args.seed,
+                   "encoder": "relu+zvc" if args.relu else "zvc"},
         "compress_GBps": round(uncompressed / (ms_c * 1e-3) / 1e9, 2),
         "decompress_GBps": round(uncompressed / (ms_d * 1e-3) / 1e9, 2),
         "compress_ms": round(ms_c, 5),
@@ -325,8 +343,8 @@ def main() -> int:
                      "traffic": traffic},
     }
     if not args.no_cpu_baseline:
-        host = x.view(torch.uint8).cpu().numpy().reshape(-1)
-        result["cpu_baseline"] = cpu_baseline(host, n, w)
+        host = x_in.view(torch.uint8).cpu().numpy().reshape(-1)
+        result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu)
     print(json.dumps(result))
     return 0
 

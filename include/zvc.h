@@ -129,6 +129,20 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
 zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream);
 
+/* Fused ReLU + compression: d_in holds PRE-activation values and the stream
+ * written is exactly the one zvc_compress would write for ReLU(d_in), without
+ * the dense ReLU output ever being stored (section 4: the zeros that ZVC
+ * removes are ReLU outputs; the offload then needs one pass over the
+ * activations instead of three).  Elements are IEEE-style numbers with the sign
+ * in the top bit: fp32 (w = 4), fp16 or bf16 (w = 2).  An element is kept,
+ * unchanged, when its sign bit is clear and it is not +0; every other element
+ * counts as zero.  So positive numbers, denormals and +inf are kept, -0.0 and
+ * negative numbers are dropped, and a NaN is kept exactly when its sign bit is
+ * clear.  zvc_decompress of the stream gives ReLU(d_in).  Arguments, errors and
+ * stream ordering as for zvc_compress. */
+zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                             uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream);
+
 /* Decompress a stream produced by zvc_compress back into n elements at d_out
  * (section 5.2, decompression engine: popcount of the mask gives the words a
  * span consumes, a prefix sum gives each slot's source, slots take a stored

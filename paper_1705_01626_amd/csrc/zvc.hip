@@ -236,21 +236,27 @@ __device__ inline uint4 load_chunk(const unsigned char* __restrict__ in, size_t 
     return make_uint4(d[0], d[1], d[2], d[3]);
 }
 
-// Presence bits of the lane's 16 bytes: bit c set <=> element c is non-zero as
-// an integer (section 5.2: words compared to zero form the mask bits).
-template <int W>
-__device__ inline unsigned presence_bits(const uint4& v) {
-    if (W == 4) {
-        return (v.x != 0u ? 1u : 0u) | (v.y != 0u ? 2u : 0u) | (v.z != 0u ? 4u : 0u) |
-               (v.w != 0u ? 8u : 0u);
-    }
+// Which elements are kept.  Plain ZVC (RELU = false) keeps the elements that are
+// non-zero as integers (section 5.2: words compared to zero form the mask
+// bits).  The fused ReLU + ZVC encoder (RELU = true) reads pre-activation
+// values (IEEE-style, sign in the top bit: fp32, fp16, bf16) and keeps those
+// whose sign bit is clear and which are not +0, i.e. the non-zeros of ReLU(x);
+// as signed integers those are exactly the words greater than zero.
+template <int W, bool RELU>
+__device__ inline bool element_kept(const uint4& v, int c) {
     const unsigned d[4] = {v.x, v.y, v.z, v.w};
+    if (W == 4) return RELU ? static_cast<int>(d[c]) > 0 : d[c] != 0u;
+    if (c & 1) return RELU ? static_cast<int>(d[c >> 1]) > 0xFFFF : d[c >> 1] > 0xFFFFu;
+    const unsigned low = d[c >> 1] & 0xFFFFu;
+    return RELU ? (low - 1u) < 0x7FFFu : low != 0u;
+}
+
+// Kept-element bits of the lane's 16 bytes: bit c set <=> element c is kept.
+template <int W, bool RELU>
+__device__ inline unsigned presence_bits(const uint4& v) {
     unsigned bits = 0;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        bits |= ((d[k] & 0xFFFFu) != 0u ? 1u : 0u) << (2 * k);
-        bits |= ((d[k] >> 16) != 0u ? 1u : 0u) << (2 * k + 1);
-    }
+    for (int c = 0; c < 16 / W; ++c) bits |= (element_kept<W, RELU>(v, c) ? 1u : 0u) << c;
     return bits;
 }
 
@@ -259,14 +265,6 @@ __device__ inline unsigned element_of(const uint4& v, int c) {
     const unsigned d[4] = {v.x, v.y, v.z, v.w};
     if (W == 4) return d[c];
     return (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
-}
-
-// Is element c of the lane's 16 bytes non-zero as an integer?
-template <int W>
-__device__ inline bool element_nonzero(const uint4& v, int c) {
-    const unsigned d[4] = {v.x, v.y, v.z, v.w};
-    if (W == 4) return d[c] != 0u;
-    return (c & 1) ? (d[c >> 1] > 0xFFFFu) : ((d[c >> 1] & 0xFFFFu) != 0u);
 }
 
 // Copies LDS bytes [shift, end) to global memory at gbase + same offsets, where
@@ -458,8 +456,8 @@ __device__ inline void finish_call(WsHeader* hdr, unsigned* counts, unsigned num
     hdr->finish[lane].value = 0u;
 }
 
-// Count of non-zero elements of input tile q, by one wave (scan self-help).
-template <int W, int LOADS, bool ALIGNED>
+// Count of kept elements of input tile q, by one wave (scan self-help).
+template <int W, int LOADS, bool ALIGNED, bool RELU>
 struct CountInputTile {
     const unsigned char* in;
     size_t n;
@@ -472,7 +470,7 @@ struct CountInputTile {
         for (int i = 0; i < LOADS * kWaves; ++i) {
             const uint4 v = load_chunk<W, ALIGNED>(
                 in, e0 + (static_cast<size_t>(i) * kWaveSize + lane) * E, n);
-            count += __popc(presence_bits<W>(v));
+            count += __popc(presence_bits<W, RELU>(v));
         }
         return static_cast<unsigned>(wave_sum(count));
     }
@@ -534,8 +532,10 @@ __device__ __forceinline__ void load_tile(uint4 (&data)[LOADS], const EncoderArg
     }
 }
 
-// Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.
-template <int W, int LOADS, bool ALIGNED>
+// Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.  With
+// RELU the input is the pre-activation tensor and the stream is that of
+// ReLU(input): the dense ReLU output is never written or read.
+template <int W, int LOADS, bool ALIGNED, bool RELU>
 __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
@@ -568,7 +568,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         unsigned bits = 0, below = 0, load_total = 0;
 #pragma unroll
         for (int c = 0; c < E; ++c) {
-            const bool nz = element_nonzero<W>(cur[j], c);
+            const bool nz = element_kept<W, RELU>(cur[j], c);
             const unsigned long long b = __ballot(nz);
             below = lanes_below(b, below);
             load_total += static_cast<unsigned>(__popcll(b));
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
 
     // ---- device-wide exclusive scan, wave 0
     if (wave == 0) {
-        const CountInputTile<W, LOADS, ALIGNED> count_tile{a.in, a.n};
+        const CountInputTile<W, LOADS, ALIGNED, RELU> count_tile{a.in, a.n};
         const unsigned long long ex = tile_exclusive_prefix(a.counts, a.prefixes, tile, tile_total,
                                                             lane, a.patience, a.hdr, count_tile);
         if (lane == 0) s_prefix = ex;
@@ -648,7 +648,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
                                 W * ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
 #pragma unroll
             for (int c = 0; c < E; ++c) {
-                const bool nz = element_nonzero<W>(cur[j], c);
+                const bool nz = element_kept<W, RELU>(cur[j], c);
                 const unsigned v = element_of<W>(cur[j], c);
                 if (__builtin_expect(nz, 1)) {   // predicated: write and advance in the kept lanes only
                     if (W == 4)
@@ -972,7 +972,7 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const unsigned char* __
     }
     unsigned long long count = 0;
 #pragma unroll
-    for (int j = 0; j < kCountLoads; ++j) count += __popc(presence_bits<W>(v[j]));
+    for (int j = 0; j < kCountLoads; ++j) count += __popc(presence_bits<W, false>(v[j]));
     count = wave_sum(count);
     if (lane == 0) s_wave[wave] = count;
     __syncthreads();
@@ -1077,14 +1077,18 @@ inline int choose_decoder_loads(size_t, int, bool) {
 }
 
 template <int W, int LOADS, bool ALIGNED>
-void launch_compress_as(hipStream_t stream, const unsigned char* in, size_t n, unsigned* masks,
-                        unsigned char* values, ScanState st, unsigned long long* d_bytes,
-                        unsigned tiles, size_t groups) {
+void launch_compress_as(bool relu, hipStream_t stream, const unsigned char* in, size_t n,
+                        unsigned* masks, unsigned char* values, ScanState st,
+                        unsigned long long* d_bytes, unsigned tiles, size_t groups) {
     const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
                            groups, g_patience.load(std::memory_order_relaxed),
                            scan_state_bytes(tiles)};
-    hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED>), dim3(tiles), dim3(kThreads), 0, stream,
-                       args);
+    if (relu)
+        hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, true>), dim3(tiles), dim3(kThreads), 0,
+                           stream, args);
+    else
+        hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, false>), dim3(tiles), dim3(kThreads), 0,
+                           stream, args);
 }
 
 template <int W, int LOADS, bool ALIGNED>
@@ -1130,6 +1134,36 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
         if (w == 4) launch_decompress_as<4, 4, true>(args...);
         else launch_decompress_as<2, 4, true>(args...);
     }
+}
+
+zvc_status compress_impl(bool relu, const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
+    if (w != 2 && w != 4) return ZVC_E_WIDTH;
+    if (d_bytes == nullptr || ((d_in == nullptr || d_out == nullptr) && n != 0)) return ZVC_E_ARG;
+    if (!aligned_to(d_in, static_cast<size_t>(w)) || !aligned_to(d_out, 4) ||
+        !aligned_to(d_bytes, 8))
+        return ZVC_E_ALIGN;
+    if (out_cap < zvc_max_compressed_bytes(n, w)) return ZVC_E_CAPACITY;
+    if (ranges_overlap(d_in, n * static_cast<size_t>(w), d_out, zvc_max_compressed_bytes(n, w)))
+        return ZVC_E_ARG;
+    if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
+    unsigned long long* out_bytes = reinterpret_cast<unsigned long long*>(d_bytes);
+    if (n == 0) {
+        hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out_bytes, 0ull);
+        return hip_ok(hipGetLastError());
+    }
+    const bool al = aligned_to(d_in, 16);
+    const int loads = choose_loads(n, w, al);
+    const size_t tiles = tiles_for(n, w, loads);
+    if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
+    // the scan state is zero between calls: the kernel cleans up after itself
+    const size_t groups = div_up(n, 32);
+    const unsigned char* in = static_cast<const unsigned char*>(d_in);
+    unsigned* masks = static_cast<unsigned*>(d_out);
+    unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
+    launch_compress(w, loads, al, relu, stream, in, n, masks, values, scan_state(d_ws, tiles), out_bytes,
+                    static_cast<unsigned>(tiles), groups);
+    return hip_ok(hipGetLastError());
 }
 
 }  // namespace
@@ -1237,32 +1271,12 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
 
 zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
-    if (w != 2 && w != 4) return ZVC_E_WIDTH;
-    if (d_bytes == nullptr || ((d_in == nullptr || d_out == nullptr) && n != 0)) return ZVC_E_ARG;
-    if (!aligned_to(d_in, static_cast<size_t>(w)) || !aligned_to(d_out, 4) ||
-        !aligned_to(d_bytes, 8))
-        return ZVC_E_ALIGN;
-    if (out_cap < zvc_max_compressed_bytes(n, w)) return ZVC_E_CAPACITY;
-    if (ranges_overlap(d_in, n * static_cast<size_t>(w), d_out, zvc_max_compressed_bytes(n, w)))
-        return ZVC_E_ARG;
-    if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
-    unsigned long long* out_bytes = reinterpret_cast<unsigned long long*>(d_bytes);
-    if (n == 0) {
-        hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out_bytes, 0ull);
-        return hip_ok(hipGetLastError());
-    }
-    const bool al = aligned_to(d_in, 16);
-    const int loads = choose_loads(n, w, al);
-    const size_t tiles = tiles_for(n, w, loads);
-    if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
-    // the scan state is zero between calls: the kernel cleans up after itself
-    const size_t groups = div_up(n, 32);
-    const unsigned char* in = static_cast<const unsigned char*>(d_in);
-    unsigned* masks = static_cast<unsigned*>(d_out);
-    unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    launch_compress(w, loads, al, stream, in, n, masks, values, scan_state(d_ws, tiles), out_bytes,
-                    static_cast<unsigned>(tiles), groups);
-    return hip_ok(hipGetLastError());
+    return compress_impl(false, d_in, n, w, d_out, out_cap, d_bytes, d_ws, ws, stream);
+}
+
+zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                             uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
+    return compress_impl(true, d_in, n, w, d_out, out_cap, d_bytes, d_ws, ws, stream);
 }
 
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,

@@ -36,6 +36,19 @@ def _abs_normal_nonzero(shape, g: torch.Generator, device) -> torch.Tensor:
     return v
 
 
+def pre_activation(post: torch.Tensor, seed: int) -> torch.Tensor:
+    """A pre-activation tensor whose ReLU is `post` (fp32, a ReLU output): every
+    zero of `post` becomes a negative draw -|N(0,1)|, a few of them -0.0 or +0.0;
+    positive elements stay as they are.  Stands in for a convolution's output
+    before its ReLU layer (section 4)."""
+    g = _gen(seed, post.device)
+    neg = torch.randn(post.shape, generator=g, device=post.device, dtype=torch.float32).abs_().neg_()
+    pick = torch.rand(post.shape, generator=g, device=post.device)
+    neg = torch.where(pick < 0.01, torch.zeros_like(neg), neg)          # +0.0
+    neg = torch.where(pick > 0.99, -torch.zeros_like(neg), neg)         # -0.0
+    return torch.where(post > 0, post, neg)
+
+
 def relu_gaussian(shape: Sequence[int], density: float, seed: int, device="cpu") -> torch.Tensor:
     """max(0, N(mu, 1)) iid, with mu chosen so that P(x > 0) = density."""
     mu = math.sqrt(2.0) * float(torch.erfinv(torch.tensor(2.0 * density - 1.0, dtype=torch.float64)))

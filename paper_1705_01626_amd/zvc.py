@@ -25,7 +25,8 @@ STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_W
 EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
-           "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count")
+           "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
+           "zvc_relu_compress")
 
 _lib = None
 
@@ -63,6 +64,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_compressed_size.argtypes = [vp, sz, ci, vp, vp, sz, vp]
     lib.zvc_compress.restype = ci
     lib.zvc_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
+    lib.zvc_relu_compress.restype = ci
+    lib.zvc_relu_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
     lib.zvc_decompress.restype = ci
     lib.zvc_decompress.argtypes = [vp, sz, sz, ci, vp, vp, sz, vp]
     lib.zvc_offload.restype = ci
@@ -161,6 +164,15 @@ def zvc_compress(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor, ws: 
     _check(load().zvc_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
                                d_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
                                _stream_handle(stream)), "zvc_compress")
+
+
+def zvc_relu_compress(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor, ws: torch.Tensor,
+                      stream=None, n: Optional[int] = None) -> None:
+    """Enqueue compression of ReLU(x) (x: fp32, fp16 or bf16 pre-activations) into `out`."""
+    n = x.numel() if n is None else n
+    _check(load().zvc_relu_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
+                                    d_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
+                                    _stream_handle(stream)), "zvc_relu_compress")
 
 
 def zvc_decompress(comp: torch.Tensor, comp_bytes: int, out: torch.Tensor, ws: torch.Tensor,
