@@ -31,6 +31,17 @@
 //      kept when its sign bit is clear and dropped when it is set (max(0, NaN)
 //      is 0 by IEEE maxNum and NaN in common frameworks: no choice matches
 //      all, this one needs no floating-point mode).
+//   6. (paper-order stream, zvc_ref_window*) section 5.1 appends a group's
+//      non-zero elements right after its mask; section 6 has the DMA engine
+//      work on windows of 4 KB of uncompressed data.  The windowed stream is
+//      that order: window after window, inside a window group after group,
+//      for each group its mask (4 bytes, little-endian, at whatever byte
+//      offset it falls on) and then its kept elements.  Windows are packed
+//      back to back with no padding, so the byte count equals that of reading
+//      1.  A table of K+1 byte offsets (window k occupies [offsets[k],
+//      offsets[k+1])) makes every window decodable on its own; the paper does
+//      not say how it finds a window, the table is this build's addition and
+//      is not counted in the compressed size.
 //
 // Entry points are extern "C" so tests can bind them with ctypes.
 
@@ -189,6 +200,94 @@ uint64_t zvc_ref_relu_compress_stream(const void* in, uint64_t n, int w, void* o
     std::vector<unsigned char> activated(static_cast<size_t>(n) * static_cast<size_t>(w));
     zvc_ref_relu(in, n, w, activated.data());
     return zvc_ref_compress_stream(activated.data(), n, w, out);
+}
+
+// Number of windows of window_elems elements covering n elements.
+uint64_t zvc_ref_window_count(uint64_t n, uint64_t window_elems) {
+    if (window_elems == 0) return 0;
+    return n / window_elems + (n % window_elems != 0 ? 1 : 0);
+}
+
+// Paper-order encoder (reading 6).  window_elems must be a positive multiple of
+// 32.  out: room for 4*groups + n*w bytes, no alignment needed.  offsets: room
+// for window_count + 1 entries.  Returns the bytes used (= offsets[last]), or
+// UINT64_MAX on a bad width or window.
+uint64_t zvc_ref_window_compress(const void* in_, uint64_t n, int w, uint64_t window_elems,
+                                 void* out_, uint64_t* offsets) {
+    if ((w != 2 && w != 4) || window_elems == 0 || window_elems % 32 != 0) return UINT64_MAX;
+    const unsigned char* in = static_cast<const unsigned char*>(in_);
+    unsigned char* out = static_cast<unsigned char*>(out_);
+    const uint64_t windows = zvc_ref_window_count(n, window_elems);
+    uint64_t pos = 0;
+    for (uint64_t k = 0; k < windows; ++k) {
+        offsets[k] = pos;
+        const uint64_t first = k * window_elems;
+        const uint64_t last = first + window_elems < n ? first + window_elems : n;
+        for (uint64_t g0 = first; g0 < last; g0 += 32) {
+            // the group's mask first ...
+            uint32_t m = 0;
+            for (int b = 0; b < 32; ++b) {
+                const uint64_t i = g0 + static_cast<uint64_t>(b);
+                if (i < last && element_bits(in, i, w) != 0) m |= (uint32_t{1} << b);
+            }
+            out[pos + 0] = static_cast<unsigned char>(m & 0xFF);
+            out[pos + 1] = static_cast<unsigned char>((m >> 8) & 0xFF);
+            out[pos + 2] = static_cast<unsigned char>((m >> 16) & 0xFF);
+            out[pos + 3] = static_cast<unsigned char>((m >> 24) & 0xFF);
+            pos += 4;
+            // ... then its non-zero elements, in order
+            for (int b = 0; b < 32; ++b) {
+                const uint64_t i = g0 + static_cast<uint64_t>(b);
+                if (i < last && element_bits(in, i, w) != 0) {
+                    std::memcpy(out + pos, in + i * w, static_cast<size_t>(w));
+                    pos += static_cast<uint64_t>(w);
+                }
+            }
+        }
+    }
+    offsets[windows] = pos;
+    return pos;
+}
+
+// Decoder for windows first_window .. first_window + num_windows - 1 of a
+// paper-order stream: reads only those windows' bytes (through the offset
+// table) and writes their elements to out, which points at the first element
+// of first_window.  Returns the number of elements written, or UINT64_MAX on
+// bad arguments.
+uint64_t zvc_ref_window_decompress(const void* stream_, const uint64_t* offsets, uint64_t n, int w,
+                                   uint64_t window_elems, uint64_t first_window,
+                                   uint64_t num_windows, void* out_) {
+    if ((w != 2 && w != 4) || window_elems == 0 || window_elems % 32 != 0) return UINT64_MAX;
+    const uint64_t windows = zvc_ref_window_count(n, window_elems);
+    if (first_window > windows || num_windows > windows - first_window) return UINT64_MAX;
+    const unsigned char* stream = static_cast<const unsigned char*>(stream_);
+    unsigned char* out = static_cast<unsigned char*>(out_);
+    uint64_t written = 0;
+    for (uint64_t k = first_window; k < first_window + num_windows; ++k) {
+        uint64_t pos = offsets[k];
+        const uint64_t first = k * window_elems;
+        const uint64_t last = first + window_elems < n ? first + window_elems : n;
+        for (uint64_t g0 = first; g0 < last; g0 += 32) {
+            const uint32_t m = static_cast<uint32_t>(stream[pos]) |
+                               (static_cast<uint32_t>(stream[pos + 1]) << 8) |
+                               (static_cast<uint32_t>(stream[pos + 2]) << 16) |
+                               (static_cast<uint32_t>(stream[pos + 3]) << 24);
+            pos += 4;
+            for (int b = 0; b < 32; ++b) {
+                const uint64_t i = g0 + static_cast<uint64_t>(b);
+                if (i >= last) break;
+                unsigned char* dst = out + (i - first_window * window_elems) * w;
+                if ((m >> b) & 1u) {
+                    std::memcpy(dst, stream + pos, static_cast<size_t>(w));
+                    pos += static_cast<uint64_t>(w);
+                } else {
+                    std::memset(dst, 0, static_cast<size_t>(w));
+                }
+                ++written;
+            }
+        }
+    }
+    return written;
 }
 
 }  // extern "C"

@@ -44,6 +44,13 @@ def load(path: Optional[str] = None) -> ctypes.CDLL:
         lib.zvc_ref_relu.argtypes = [vp, _U64, ip, vp]
         lib.zvc_ref_relu_compress_stream.restype = _U64
         lib.zvc_ref_relu_compress_stream.argtypes = [vp, _U64, ip, vp]
+    if hasattr(lib, "zvc_ref_window_compress"):
+        lib.zvc_ref_window_count.restype = _U64
+        lib.zvc_ref_window_count.argtypes = [_U64, _U64]
+        lib.zvc_ref_window_compress.restype = _U64
+        lib.zvc_ref_window_compress.argtypes = [vp, _U64, ip, _U64, vp, vp]
+        lib.zvc_ref_window_decompress.restype = _U64
+        lib.zvc_ref_window_decompress.argtypes = [vp, vp, _U64, ip, _U64, _U64, _U64, vp]
     _lib_cache[path] = lib
     return lib
 
@@ -142,3 +149,39 @@ def relu_compress_stream(x: np.ndarray, w: int, lib=None) -> np.ndarray:
     if used == _BAD:
         raise ValueError("unsupported element width %r" % (w,))
     return out[:used].copy()
+
+
+def window_count(n: int, window_elems: int, lib=None) -> int:
+    return int((lib or load()).zvc_ref_window_count(n, window_elems))
+
+
+def window_compress(x: np.ndarray, w: int, window_elems: int, lib=None) -> Tuple[np.ndarray, np.ndarray]:
+    """Paper-order windowed stream of the raw bytes of `x`.
+
+    Returns (stream uint8[bytes], offsets uint64[windows + 1])."""
+    lib = lib or load()
+    raw = _as_bytes(x)
+    n = raw.size // w
+    out = np.zeros(4 * groups(n, lib) + n * w + 1, dtype=np.uint8)
+    windows = window_count(n, window_elems, lib) if window_elems else 0
+    offsets = np.zeros(windows + 1, dtype=np.uint64)
+    used = lib.zvc_ref_window_compress(_ptr(raw), n, w, window_elems, _ptr(out), _ptr(offsets))
+    if used == _BAD:
+        raise ValueError("unsupported width %r or window %r" % (w, window_elems))
+    return out[:used].copy(), offsets
+
+
+def window_decompress(stream: np.ndarray, offsets: np.ndarray, n: int, w: int, window_elems: int,
+                      first_window: int, num_windows: int, lib=None) -> np.ndarray:
+    """Elements of windows [first_window, first_window + num_windows) as uint8 bytes."""
+    lib = lib or load()
+    comp = _as_bytes(stream) if stream.size else np.zeros(1, dtype=np.uint8)
+    offs = np.ascontiguousarray(offsets, dtype=np.uint64)
+    elems = max(0, min(n, (first_window + num_windows) * window_elems) - first_window * window_elems)
+    out = np.full(max(elems * w, 1), 0xAB, dtype=np.uint8)
+    got = lib.zvc_ref_window_decompress(_ptr(comp), _ptr(offs), n, w, window_elems, first_window,
+                                        num_windows, _ptr(out))
+    if got == _BAD:
+        raise ValueError("bad window arguments")
+    assert got == elems
+    return out[: elems * w]

@@ -30,10 +30,14 @@ def load_handbuilt(filename="handbuilt_cases.txt"):
             if key == "case":
                 cur = {"name": rest}
                 cases.append(cur)
-            elif key in ("n", "w", "bytes"):
+            elif key in ("n", "w", "bytes", "window"):
                 cur[key] = int(rest)
             elif key in ("in", "relu"):
                 cur[key] = _words(toks, cur["w"])
+            elif key == "stream":
+                cur["stream"] = np.array([int(t, 16) for t in toks], dtype=np.uint8)
+            elif key == "offsets":
+                cur["offsets"] = np.array([int(t) for t in toks], dtype=np.uint64)
             elif key == "masks":
                 cur["masks"] = _words(toks, 4)
             elif key == "values":
@@ -41,6 +45,10 @@ def load_handbuilt(filename="handbuilt_cases.txt"):
     for c in cases:
         assert c["in"].size == c["n"], c["name"]
     return cases
+
+
+def load_window_cases():
+    return load_handbuilt("window_cases.txt")
 
 
 def load_relu_cases():

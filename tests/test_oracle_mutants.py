@@ -10,7 +10,8 @@ from oracle import build as oracle_build
 from oracle import zvc_ref
 from tests import test_oracle as pins
 from tests import test_oracle_relu as relu_pins
-from tests.golden_cases import load_handbuilt, load_relu_cases
+from tests import test_oracle_window as window_pins
+from tests.golden_cases import load_handbuilt, load_relu_cases, load_window_cases
 
 MUTANTS = [
     ("msb_first_bit_order", "m |= (uint32_t{1} << b);", "m |= (uint32_t{1} << (31 - b));"),
@@ -44,6 +45,16 @@ MUTANTS = [
      "const uint32_t sign = w == 4 ? 0x80000000u : 0x4000u;"),
     ("relu_leaves_dropped_elements_in_place", "std::memset(out + i * w, 0, static_cast<size_t>(w));\n    }\n    return 0;",
      "(void)0;\n    }\n    return 0;"),
+    ("window_values_before_their_mask", "            pos += 4;\n            // ... then its non-zero elements, in order",
+     "            // ... then its non-zero elements, in order"),
+    ("window_encoder_drops_ragged_last_group", "        offsets[k] = pos;\n        const uint64_t first = k * window_elems;\n        const uint64_t last = first + window_elems < n ? first + window_elems : n;\n        for (uint64_t g0 = first; g0 < last; g0 += 32) {",
+     "        offsets[k] = pos;\n        const uint64_t first = k * window_elems;\n        const uint64_t last = first + window_elems < n ? first + window_elems : n;\n        for (uint64_t g0 = first; g0 + 32 <= last; g0 += 32) {"),
+    ("window_offsets_one_late", "        offsets[k] = pos;\n        const uint64_t first = k * window_elems;\n        const uint64_t last = first + window_elems < n ? first + window_elems : n;\n        for (uint64_t g0 = first; g0 < last; g0 += 32) {\n            // the group's mask first ...",
+     "        offsets[k] = pos + 4;\n        const uint64_t first = k * window_elems;\n        const uint64_t last = first + window_elems < n ? first + window_elems : n;\n        for (uint64_t g0 = first; g0 < last; g0 += 32) {\n            // the group's mask first ..."),
+    ("window_decoder_starts_at_stream_start", "        uint64_t pos = offsets[k];\n        const uint64_t first = k * window_elems;\n        const uint64_t last = first + window_elems < n ? first + window_elems : n;\n        for (uint64_t g0 = first; g0 < last; g0 += 32) {\n            const uint32_t m =",
+     "        uint64_t pos = offsets[first_window];\n        const uint64_t first = k * window_elems;\n        const uint64_t last = first + window_elems < n ? first + window_elems : n;\n        for (uint64_t g0 = first; g0 < last; g0 += 32) {\n            const uint32_t m ="),
+    ("window_big_endian_mask", "            out[pos + 0] = static_cast<unsigned char>(m & 0xFF);\n            out[pos + 1] = static_cast<unsigned char>((m >> 8) & 0xFF);",
+     "            out[pos + 1] = static_cast<unsigned char>(m & 0xFF);\n            out[pos + 0] = static_cast<unsigned char>((m >> 8) & 0xFF);"),
     ("fused_skips_relu", "return zvc_ref_compress_stream(activated.data(), n, w, out);",
      "return zvc_ref_compress_stream(in, n, w, out);"),
 ]
@@ -67,6 +78,12 @@ def _pin_suite(oracle):
     pins.test_layout_independence(oracle)
     pins.test_random_byte_soup_round_trip(oracle)
     pins.test_values_preserve_order(oracle)
+    for case in load_window_cases():
+        window_pins.test_window_handbuilt_cases(oracle, case)
+    for w in (2, 4):
+        for n in (33, 1025, 4097):
+            window_pins.test_window_stream_holds_the_planar_masks_and_values(oracle, n, w)
+        window_pins.test_any_window_range_decodes_on_its_own(oracle, w)
     for case in load_relu_cases():
         relu_pins.test_relu_handbuilt_cases(oracle, case)
     relu_pins.test_relu_matches_numpy_maximum_fp32(oracle)
@@ -79,7 +96,8 @@ def _pin_suite(oracle):
 def _bound(lib):
     ns = types.SimpleNamespace()
     for name in ("groups", "compressed_bytes", "compress", "compress_stream", "decompress",
-                 "decompress_stream", "count_nonzero", "relu", "relu_compress_stream"):
+                 "decompress_stream", "count_nonzero", "relu", "relu_compress_stream", "window_count", "window_compress",
+                 "window_decompress"):
         fn = getattr(zvc_ref, name)
         setattr(ns, name, (lambda f: lambda *a: f(*a, lib=lib))(fn))
     return ns
