@@ -64,7 +64,8 @@ def event_timed(fn, reps: int, torch) -> float:
     return start.elapsed_time(stop) / reps
 
 
-def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool = False):
+def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool = False,
+                 windowed: bool = False):
     """The oracle as it stands, single thread, on the same bytes: whole-tensor
     compress + decompress round trips until about `budget_s` seconds are spent.
     With `relu` the encoder is the oracle's fused ReLU + ZVC (ReLU into a
@@ -79,9 +80,18 @@ def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool 
     reps, spent, best = 0, 0.0, None
     while reps < 1 or (spent < budget_s and reps < 50):
         t0 = time.perf_counter()
-        encode = lib.zvc_ref_relu_compress_stream if relu else lib.zvc_ref_compress_stream
-        encode(vp(host_bytes.ctypes.data), n, w, vp(comp.ctypes.data))
-        lib.zvc_ref_decompress_stream(vp(comp.ctypes.data), n, w, vp(back.ctypes.data))
+        if windowed:
+            per = 4096 // w
+            windows = (n + per - 1) // per
+            offsets = np.zeros(windows + 1, dtype=np.uint64)
+            lib.zvc_ref_window_compress(vp(host_bytes.ctypes.data), n, w, per, vp(comp.ctypes.data),
+                                        vp(offsets.ctypes.data))
+            lib.zvc_ref_window_decompress(vp(comp.ctypes.data), vp(offsets.ctypes.data), n, w, per, 0,
+                                          windows, vp(back.ctypes.data))
+        else:
+            encode = lib.zvc_ref_relu_compress_stream if relu else lib.zvc_ref_compress_stream
+            encode(vp(host_bytes.ctypes.data), n, w, vp(comp.ctypes.data))
+            lib.zvc_ref_decompress_stream(vp(comp.ctypes.data), n, w, vp(back.ctypes.data))
         dt = time.perf_counter() - t0
         spent += dt
         reps += 1
@@ -223,6 +233,9 @@ def main() -> int:
     ap.add_argument("--relu", action="store_true",
                     help="time the fused ReLU + ZVC encoder on pre-activations of the workload "
                          "(zeros of the tensor replaced by negative values)")
+    ap.add_argument("--windowed", action="store_true",
+                    help="time the paper-order windowed stream (zvc_window_compress / "
+                         "zvc_window_decompress of all windows) instead of the planar one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
     ap.add_argument("--counter-pass", action="store_true",
@@ -250,8 +263,17 @@ def main() -> int:
         x_in = workloads.pre_activation(x.float(), args.seed + 1).to(x.dtype)
         x = torch.relu(x_in)          # what the round trip must give back
         described += "; pre-activations (zeros replaced by negative draws), fused ReLU + ZVC encoder"
+    if args.relu and args.windowed:
+        raise SystemExit("bench.py: --relu and --windowed are separate modes")
     encode = zvc.zvc_relu_compress if args.relu else zvc.zvc_compress
     n, w = x.numel(), x.element_size()
+    if args.windowed:
+        windows = zvc.zvc_window_count(n, w)
+        offsets = torch.zeros(windows + 1, dtype=torch.int64, device=dev)
+        described += "; paper-order stream in 4 KB windows with an offset table"
+
+        def encode(t, c, b, s):
+            zvc.zvc_window_compress(t, c, offsets, b, s)
     ws = zvc.new_workspace(n, w, dev)
     comp = zvc.new_compressed_buffer(n, w, dev)
     d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -267,7 +289,10 @@ def main() -> int:
         encode(x_in, comp, d_bytes, ws)
 
     def decompress():
-        zvc.zvc_decompress(comp, nbytes, out, ws)
+        if args.windowed:
+            zvc.zvc_window_decompress(comp, nbytes, offsets, n, 0, windows, out)
+        else:
+            zvc.zvc_decompress(comp, nbytes, out, ws)
 
     def step():
         compress()
@@ -329,7 +354,8 @@ def main() -> int:
                    "element_bytes": w, "uncompressed_bytes": uncompressed,
                    "compressed_bytes": nbytes, "density": round(density, 6),
                    "compression_ratio": round(uncompressed / nbytes, 4), "seed": args.seed,
-                   "encoder": "relu+zvc" if args.relu else "zvc"},
+                   "encoder": "relu+zvc" if args.relu else "zvc",
+                   "stream": "windowed" if args.windowed else "planar"},
         "compress_GBps": round(uncompressed / (ms_c * 1e-3) / 1e9, 2),
         "decompress_GBps": round(uncompressed / (ms_d * 1e-3) / 1e9, 2),
         "compress_ms": round(ms_c, 5),
@@ -344,7 +370,7 @@ def main() -> int:
     }
     if not args.no_cpu_baseline:
         host = x_in.view(torch.uint8).cpu().numpy().reshape(-1)
-        result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu)
+        result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu, windowed=args.windowed)
     print(json.dumps(result))
     return 0
 

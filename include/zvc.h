@@ -152,6 +152,43 @@ zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, siz
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,
                           void* d_ws, size_t ws, hipStream_t stream);
 
+/* ---- the paper's own stream order, in independently decodable windows ------ */
+
+/* Section 5.1 appends a group's non-zero elements right after its mask, and the
+ * DMA engine of section 6 works on windows of 4 KB of uncompressed data.  The
+ * windowed stream is that order: window after window (4096 / w elements each,
+ * the last one possibly shorter), inside a window group after group, for each
+ * group its 32-bit mask (little-endian; for w = 2 it may fall on a 2-byte
+ * boundary) and then its kept elements.  Windows are packed back to back, so
+ * the stream has exactly the bytes of the planar one, 4*ceil(n/32) + w*nnz.
+ * Beside it goes a table of zvc_window_count(n, w) + 1 byte offsets: window k
+ * occupies [offsets[k], offsets[k+1]) and the last entry is the stream's size.
+ * The table (this library's addition, not counted in the compressed size)
+ * makes any range of windows decodable without touching the rest. */
+
+/* Number of windows for n elements of width w: ceil(n*w / 4096).  0 for a bad w. */
+size_t zvc_window_count(size_t n, int w);
+
+/* Compress into the windowed stream.  d_out / out_cap / d_bytes / workspace as
+ * for zvc_compress; d_offsets is a device array of zvc_window_count(n, w) + 1
+ * 64-bit words (8-byte aligned, not overlapping the other buffers). */
+zvc_status zvc_window_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                               uint64_t* d_offsets, uint64_t* d_bytes, void* d_ws, size_t ws,
+                               hipStream_t stream);
+
+/* Decompress windows first_window .. first_window + num_windows - 1 of a
+ * windowed stream of n elements (a partial prefetch).  d_stream points at the
+ * START of the stream (aligned to w) and stream_bytes is the number of readable
+ * bytes there; d_offsets is the whole table.  d_out receives the elements of
+ * those windows only, i.e. it points at where element first_window * 4096 / w
+ * of the tensor goes.  Needs no workspace.  The kernel reads nothing outside
+ * [d_stream, d_stream + stream_bytes) and the table entries of the windows
+ * asked for; what a damaged table or mask asks for beyond a window's bytes
+ * decodes as zero.  ZVC_E_ARG if the range does not lie within the windows. */
+zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, const uint64_t* d_offsets,
+                                 size_t n, int w, size_t first_window, size_t num_windows,
+                                 void* d_out, hipStream_t stream);
+
 /* Offload (section 3 and section 5.4: the activation map leaves GPU memory as
  * a compressed copy whose size is known on completion).  Compresses d_in into
  * the device staging buffer d_stage on `compute`, waits ON THE HOST for the

@@ -506,6 +506,7 @@ struct EncoderArgs {
     size_t num_groups;
     unsigned patience;
     size_t state_bytes;
+    unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
 };
 
 // Issues the loads of `tile`: LOADS x 16 bytes per lane, 1 KB per wave
@@ -535,13 +536,27 @@ __device__ __forceinline__ void load_tile(uint4 (&data)[LOADS], const EncoderArg
 // Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.  With
 // RELU the input is the pre-activation tensor and the stream is that of
 // ReLU(input): the dense ReLU output is never written or read.
-template <int W, int LOADS, bool ALIGNED, bool RELU>
+//
+// WINDOWED selects the paper's own stream order (section 5.1: a group's
+// non-zeros are appended right after its mask) in windows of 4 KB of input
+// (section 6), packed back to back, plus a table with the byte offset of every
+// window.  A window is what one wave stages at a time (4 loads), so the only
+// differences are where things go in the wave's LDS slice -- the mask of group
+// g of the window sits before the group's elements, i.e. after g masks and all
+// earlier kept elements -- and that masks leave with the values instead of going
+// to a mask area.  The scan is the same: a window's byte offset is 4 x (groups
+// before it) + W x (kept elements before it).
+template <int W, int LOADS, bool ALIGNED, bool RELU, bool WINDOWED>
 __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
+    constexpr int kStepGroups = G::kEncStageLoads * G::kGroupsPerLoad;   // masks of one window: 32 | 64
+    constexpr int kMaskUnits = 4 / W;                                    // a mask in units of W bytes
+    static_assert(!WINDOWED || G::kEncStageLoads == 4, "a window is four loads of a wave (4 KB)");
 
-    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kEncWaveStageBytes];
+    __shared__ __align__(16) unsigned char
+        s_stage[kWaves][G::kEncWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0)];
     __shared__ unsigned s_wave_total[kWaves];
     __shared__ unsigned long long s_prefix;
 
@@ -594,14 +609,16 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
 #pragma unroll
     for (int j = 0; j < LOADS; ++j)
         asm volatile("" : "+v"(cur[j].x), "+v"(cur[j].y), "+v"(cur[j].z), "+v"(cur[j].w));
+    if (!WINDOWED) {
 #pragma unroll
-    for (int q = 0; q < G::kMaskRegs; ++q) {
-        const int j = q * LPG + lane_in_group;  // the load whose mask this lane kept
-        if (j < LOADS) {
-            const size_t g = static_cast<size_t>(tile) * G::kTileGroups +
-                             static_cast<size_t>(wave * LOADS + j) * G::kGroupsPerLoad +
-                             lane / LPG;
-            if (g < a.num_groups) __builtin_nontemporal_store(my_mask[q], a.masks + g);
+        for (int q = 0; q < G::kMaskRegs; ++q) {
+            const int j = q * LPG + lane_in_group;  // the load whose mask this lane kept
+            if (j < LOADS) {
+                const size_t g = static_cast<size_t>(tile) * G::kTileGroups +
+                                 static_cast<size_t>(wave * LOADS + j) * G::kGroupsPerLoad +
+                                 lane / LPG;
+                if (g < a.num_groups) __builtin_nontemporal_store(my_mask[q], a.masks + g);
+            }
         }
     }
     // ---- tile-level scan of the wave totals
@@ -639,13 +656,41 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     for (int h = 0; h < G::kEncStageSteps; ++h) {
         const unsigned first_rank = run[h * G::kEncStageLoads];
         const unsigned step_total = run[(h + 1) * G::kEncStageLoads] - first_rank;
-        unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W;  // wave-uniform
+        // windowed: the step is window `window`, whose groups may end with the tensor
+        const size_t window = (static_cast<size_t>(tile) * kWaves + wave) * G::kEncStageSteps + h;
+        const size_t window_group0 = window * kStepGroups;
+        const unsigned valid_groups =
+            !WINDOWED || window_group0 >= a.num_groups ? 0u
+            : a.num_groups - window_group0 < kStepGroups ? static_cast<unsigned>(a.num_groups - window_group0)
+                                                         : static_cast<unsigned>(kStepGroups);
+        const unsigned step_bytes = step_total * W + 4u * valid_groups;
+        unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W +   // wave-uniform
+                             (WINDOWED ? 4 * (window_group0 < a.num_groups ? window_group0 : a.num_groups) : 0);
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
+        if (WINDOWED && valid_groups != 0 && lane == 0)
+            a.offsets[window] = static_cast<unsigned long long>(dst - a.values);
 #pragma unroll
         for (int jj = 0; jj < G::kEncStageLoads; ++jj) {
             const int j = h * G::kEncStageLoads + jj;
-            unsigned char* at = stage + (shift + W * (run[j] - first_rank)) +
-                                W * ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
+            // rank of the lane's first element within the step
+            const unsigned rank0 = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
+            const unsigned group = static_cast<unsigned>(jj * G::kGroupsPerLoad + lane / LPG);
+            unsigned char* at = stage + shift + W * (rank0 + (WINDOWED ? kMaskUnits * (group + 1u) : 0u));
+            if (WINDOWED) {
+                // the lane that kept this load's mask puts it before the group's elements,
+                // whose first rank the group's first lane knows
+                const unsigned group_rank0 = __shfl(rank0, lane - lane_in_group);
+                if (lane_in_group == j % LPG && group < valid_groups) {
+                    unsigned char* mask_at = stage + shift + W * (group_rank0 + kMaskUnits * group);
+                    const unsigned m = my_mask[j / LPG];
+                    if (W == 4) {
+                        *reinterpret_cast<unsigned*>(mask_at) = m;
+                    } else {
+                        *reinterpret_cast<unsigned short*>(mask_at) = static_cast<unsigned short>(m);
+                        *reinterpret_cast<unsigned short*>(mask_at + 2) = static_cast<unsigned short>(m >> 16);
+                    }
+                }
+            }
 #pragma unroll
             for (int c = 0; c < E; ++c) {
                 const bool nz = element_kept<W, RELU>(cur[j], c);
@@ -661,14 +706,18 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
             __builtin_amdgcn_sched_barrier(0);
         }
         wave_lds_sync();
-        wave_copy_out<W>(dst - shift, stage, shift, shift + step_total * W, lane);
+        wave_copy_out<W>(dst - shift, stage, shift, shift + step_bytes, lane);
         wave_lds_sync();
     }
     ZVC_TRACE_POINT(tile, 5);
 
     // ---- section 5.4: the compressed size, reported by the last tile
-    if (tile == a.num_tiles - 1 && tid == 0)
-        *a.d_bytes = 4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
+    if (tile == a.num_tiles - 1 && tid == 0) {
+        const unsigned long long total =
+            4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
+        *a.d_bytes = total;
+        if (WINDOWED) a.offsets[div_up(a.num_groups, kStepGroups)] = total;
+    }
 
     if (tile == a.num_tiles - 1 && wave == 0)
         finish_call(a.hdr, a.counts, a.num_tiles, lane, a.state_bytes);
@@ -937,6 +986,122 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     }
 }
 
+// Decoder of the windowed stream.  One wave per window, no scan and no
+// pre-pass: the offset table says where a window's bytes are, and a window
+// decodes from its own bytes alone (section 5.2: the popcount of a mask gives
+// the offset of the next mask).  The wave stages the window's bytes in LDS,
+// lane 0 walks the masks one after the other -- the serial chain the paper's
+// decoder has too, here at most 64 steps through LDS -- and leaves every
+// mask and the position of its first element for the other lanes, which then
+// rebuild 16 bytes of output per load as in the planar decoder.  Reads stay
+// inside [0, stream_bytes) and inside the staged window whatever the table and
+// the masks say; what a damaged stream asks for beyond that decodes as zero.
+constexpr int kWindowBytes = 4096;      // uncompressed bytes per window (section 6)
+
+template <int W, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void window_decode_kernel(
+    const unsigned char* __restrict__ stream, unsigned long long stream_bytes,
+    const unsigned long long* __restrict__ offsets, size_t n, size_t num_groups,
+    size_t first_window, size_t num_windows, unsigned char* __restrict__ out) {
+    constexpr int E = 16 / W;
+    constexpr int LPG = 32 / E;
+    constexpr int GPL = kWaveSize / LPG;
+    constexpr int kStepGroups = kStageLoads * GPL;          // masks per window: 32 | 64
+    constexpr int kWindowElems = kStepGroups * 32;
+    constexpr unsigned kMaxBytes = kWindowBytes + 4 * kStepGroups;
+    static_assert(kWindowElems * W == kWindowBytes, "a window is one staging step of a wave");
+
+    __shared__ __align__(16) unsigned char s_stage[kWaves][kMaxBytes + 16];
+    __shared__ unsigned s_mask[kWaves][kStepGroups];
+    __shared__ unsigned s_first[kWaves][kStepGroups];      // LDS offset of the group's first stored element
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
+    const size_t local = static_cast<size_t>(blockIdx.x) * kWaves + wave;
+    if (local >= num_windows) return;
+    const size_t window = first_window + local;
+    const size_t group0 = window * kStepGroups;
+    const unsigned valid_groups = group0 >= num_groups ? 0u
+        : num_groups - group0 < kStepGroups ? static_cast<unsigned>(num_groups - group0)
+                                            : static_cast<unsigned>(kStepGroups);
+
+    // ---- the window's bytes, clamped to what can be there
+    unsigned long long lo = offsets[window], hi = offsets[window + 1];
+    if (lo > stream_bytes) lo = stream_bytes;
+    if (hi > stream_bytes) hi = stream_bytes;
+    if (hi < lo) hi = lo;
+    const unsigned bytes = hi - lo > kMaxBytes ? kMaxBytes : static_cast<unsigned>(hi - lo);
+    const unsigned char* src = stream + lo;    // wave-uniform, aligned to W
+    const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
+    const unsigned limit = shift + bytes;
+    unsigned char* stage = s_stage[wave];
+    wave_copy_in<W>(stage, src - shift, shift, limit, limit, lane);
+    wave_lds_sync();
+
+    // ---- the serial walk over the masks
+    if (lane == 0) {
+        unsigned p = shift;
+        for (unsigned g = 0; g < static_cast<unsigned>(kStepGroups); ++g) {
+            unsigned m = 0;
+            if (g < valid_groups && p + 4u <= limit) {
+                if (W == 4)
+                    m = *reinterpret_cast<const unsigned*>(stage + p);
+                else
+                    m = *reinterpret_cast<const unsigned short*>(stage + p) |
+                        (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(stage + p + 2)) << 16);
+            }
+            s_mask[wave][g] = m;
+            s_first[wave][g] = p + 4u;
+            p += 4u + W * __popc(m);
+        }
+    }
+    wave_lds_sync();
+
+    // ---- expand
+    const size_t window_elem0 = window * kWindowElems;           // in the tensor
+    unsigned char* wout = out + local * kWindowBytes;            // this window's output
+    const bool full = ALIGNED && window_elem0 + kWindowElems <= n;
+#pragma unroll
+    for (int jj = 0; jj < kStageLoads; ++jj) {
+        const unsigned in_window = static_cast<unsigned>((jj * kWaveSize + lane) * E);   // element within the window
+        const int gl = jj * GPL + lane / LPG;
+        const unsigned gm = s_mask[wave][gl];
+        const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
+        unsigned at = s_first[wave][gl] + W * __popc(gm & ((1u << bit0) - 1u));
+        const unsigned field = gm >> bit0;
+        unsigned d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int c = 0; c < E; ++c) {
+            const bool set = ((field >> c) & 1u) != 0u && at + W <= limit;
+            const unsigned from = set ? at : shift;
+            if (W == 4) {
+                const unsigned v = *reinterpret_cast<const unsigned*>(stage + from);
+                d[c] = set ? v : 0u;
+            } else {
+                const unsigned v = *reinterpret_cast<const unsigned short*>(stage + from);
+                d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
+            }
+            at += ((field >> c) & 1u) ? W : 0;
+        }
+        const size_t e0 = window_elem0 + in_window;
+        if (full || (ALIGNED && e0 + E <= n)) {
+            store16_stream(wout + in_window * W, make_uint4(d[0], d[1], d[2], d[3]));
+        } else {
+#pragma unroll
+            for (int c = 0; c < E; ++c) {
+                if (e0 + c < n) {
+                    if (W == 4)
+                        reinterpret_cast<unsigned*>(wout)[in_window + c] = d[c];
+                    else
+                        reinterpret_cast<unsigned short*>(wout)[in_window + c] = static_cast<unsigned short>(
+                            (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
+                }
+            }
+        }
+    }
+}
+
 // Count-only pass (section 5.4's size, without producing the stream).  One
 // workgroup per 32 KB of input, all of a thread's loads in flight together.
 // A workgroup adds (1 << 40) + its count to one of 64 accumulators with a single
@@ -1076,19 +1241,28 @@ inline int choose_decoder_loads(size_t, int, bool) {
     return ZVC_FORCE_DECODER_LOADS != 0 ? ZVC_FORCE_DECODER_LOADS : kMinLoads;
 }
 
+enum class Encoder { kPlain, kRelu, kWindowed };
+
 template <int W, int LOADS, bool ALIGNED>
-void launch_compress_as(bool relu, hipStream_t stream, const unsigned char* in, size_t n,
+void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
                         unsigned* masks, unsigned char* values, ScanState st,
-                        unsigned long long* d_bytes, unsigned tiles, size_t groups) {
+                        unsigned long long* d_bytes, unsigned tiles, size_t groups,
+                        unsigned long long* offsets) {
     const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
                            groups, g_patience.load(std::memory_order_relaxed),
-                           scan_state_bytes(tiles)};
-    if (relu)
-        hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, true>), dim3(tiles), dim3(kThreads), 0,
-                           stream, args);
-    else
-        hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, false>), dim3(tiles), dim3(kThreads), 0,
-                           stream, args);
+                           scan_state_bytes(tiles), offsets};
+    const dim3 grid(tiles), block(kThreads);
+    switch (mode) {
+        case Encoder::kPlain:
+            hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, false, false>), grid, block, 0, stream, args);
+            break;
+        case Encoder::kRelu:
+            hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, true, false>), grid, block, 0, stream, args);
+            break;
+        case Encoder::kWindowed:
+            hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, false, true>), grid, block, 0, stream, args);
+            break;
+    }
 }
 
 template <int W, int LOADS, bool ALIGNED>
@@ -1136,8 +1310,9 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
     }
 }
 
-zvc_status compress_impl(bool relu, const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
-                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
+zvc_status compress_impl(Encoder mode, const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                         uint64_t* d_bytes, uint64_t* d_offsets, void* d_ws, size_t ws,
+                         hipStream_t stream) {
     if (w != 2 && w != 4) return ZVC_E_WIDTH;
     if (d_bytes == nullptr || ((d_in == nullptr || d_out == nullptr) && n != 0)) return ZVC_E_ARG;
     if (!aligned_to(d_in, static_cast<size_t>(w)) || !aligned_to(d_out, 4) ||
@@ -1150,6 +1325,9 @@ zvc_status compress_impl(bool relu, const void* d_in, size_t n, int w, void* d_o
     unsigned long long* out_bytes = reinterpret_cast<unsigned long long*>(d_bytes);
     if (n == 0) {
         hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out_bytes, 0ull);
+        if (mode == Encoder::kWindowed)
+            hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream,
+                               reinterpret_cast<unsigned long long*>(d_offsets), 0ull);
         return hip_ok(hipGetLastError());
     }
     const bool al = aligned_to(d_in, 16);
@@ -1161,8 +1339,10 @@ zvc_status compress_impl(bool relu, const void* d_in, size_t n, int w, void* d_o
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
     unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    launch_compress(w, loads, al, relu, stream, in, n, masks, values, scan_state(d_ws, tiles), out_bytes,
-                    static_cast<unsigned>(tiles), groups);
+    launch_compress(w, loads, al, mode, stream, in, n, masks,
+                    mode == Encoder::kWindowed ? static_cast<unsigned char*>(d_out) : values,
+                    scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups,
+                    reinterpret_cast<unsigned long long*>(d_offsets));
     return hip_ok(hipGetLastError());
 }
 
@@ -1271,12 +1451,66 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
 
 zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
-    return compress_impl(false, d_in, n, w, d_out, out_cap, d_bytes, d_ws, ws, stream);
+    return compress_impl(Encoder::kPlain, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws, stream);
 }
 
 zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                              uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
-    return compress_impl(true, d_in, n, w, d_out, out_cap, d_bytes, d_ws, ws, stream);
+    return compress_impl(Encoder::kRelu, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws, stream);
+}
+
+size_t zvc_window_count(size_t n, int w) {
+    if (w != 2 && w != 4) return 0;
+    return div_up(n * static_cast<size_t>(w), kWindowBytes);
+}
+
+zvc_status zvc_window_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                               uint64_t* d_offsets, uint64_t* d_bytes, void* d_ws, size_t ws,
+                               hipStream_t stream) {
+    if (d_offsets == nullptr) return ZVC_E_ARG;
+    if (!aligned_to(d_offsets, 8)) return ZVC_E_ALIGN;
+    if (w == 2 || w == 4) {
+        const size_t table = 8 * (zvc_window_count(n, w) + 1);
+        if (ranges_overlap(d_offsets, table, d_out, zvc_max_compressed_bytes(n, w)) ||
+            ranges_overlap(d_offsets, table, d_in, n * static_cast<size_t>(w)))
+            return ZVC_E_ARG;
+    }
+    return compress_impl(Encoder::kWindowed, d_in, n, w, d_out, out_cap, d_bytes, d_offsets, d_ws, ws,
+                         stream);
+}
+
+zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, const uint64_t* d_offsets,
+                                 size_t n, int w, size_t first_window, size_t num_windows,
+                                 void* d_out, hipStream_t stream) {
+    if (w != 2 && w != 4) return ZVC_E_WIDTH;
+    const size_t windows = zvc_window_count(n, w);
+    if (first_window > windows || num_windows > windows - first_window) return ZVC_E_ARG;
+    if (num_windows == 0) return ZVC_OK;
+    if (d_stream == nullptr || d_offsets == nullptr || d_out == nullptr) return ZVC_E_ARG;
+    if (!aligned_to(d_out, static_cast<size_t>(w)) || !aligned_to(d_stream, static_cast<size_t>(w)) ||
+        !aligned_to(d_offsets, 8))
+        return ZVC_E_ALIGN;
+    const size_t elems_per_window = kWindowBytes / static_cast<size_t>(w);
+    const size_t last_elem = (first_window + num_windows) * elems_per_window < n
+                                 ? (first_window + num_windows) * elems_per_window : n;
+    const size_t out_bytes = (last_elem - first_window * elems_per_window) * static_cast<size_t>(w);
+    if (ranges_overlap(d_stream, stream_bytes, d_out, out_bytes)) return ZVC_E_ARG;
+    const size_t blocks = div_up(num_windows, kWaves);
+    if (blocks > 0x7FFFFFFFull) return ZVC_E_ARG;
+    const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+    const unsigned char* in = static_cast<const unsigned char*>(d_stream);
+    const unsigned long long* offs = reinterpret_cast<const unsigned long long*>(d_offsets);
+    unsigned char* out = static_cast<unsigned char*>(d_out);
+    const size_t groups = div_up(n, 32);
+    const bool al = aligned_to(d_out, 16);
+    if (w == 4) {
+        if (al) hipLaunchKernelGGL((window_decode_kernel<4, true>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
+        else hipLaunchKernelGGL((window_decode_kernel<4, false>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
+    } else {
+        if (al) hipLaunchKernelGGL((window_decode_kernel<2, true>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
+        else hipLaunchKernelGGL((window_decode_kernel<2, false>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
+    }
+    return hip_ok(hipGetLastError());
 }
 
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,

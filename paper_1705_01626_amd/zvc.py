@@ -26,7 +26,7 @@ EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
            "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
-           "zvc_relu_compress")
+           "zvc_relu_compress", "zvc_window_count", "zvc_window_compress", "zvc_window_decompress")
 
 _lib = None
 
@@ -64,6 +64,12 @@ def load() -> ctypes.CDLL:
     lib.zvc_compressed_size.argtypes = [vp, sz, ci, vp, vp, sz, vp]
     lib.zvc_compress.restype = ci
     lib.zvc_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
+    lib.zvc_window_count.restype = sz
+    lib.zvc_window_count.argtypes = [sz, ci]
+    lib.zvc_window_compress.restype = ci
+    lib.zvc_window_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, vp, sz, vp]
+    lib.zvc_window_decompress.restype = ci
+    lib.zvc_window_decompress.argtypes = [vp, sz, vp, sz, ci, sz, sz, vp, vp]
     lib.zvc_relu_compress.restype = ci
     lib.zvc_relu_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
     lib.zvc_decompress.restype = ci
@@ -173,6 +179,36 @@ def zvc_relu_compress(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor,
     _check(load().zvc_relu_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
                                     d_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
                                     _stream_handle(stream)), "zvc_relu_compress")
+
+
+def zvc_window_count(n: int, w: int) -> int:
+    return int(load().zvc_window_count(n, w))
+
+
+def zvc_window_compress(x: torch.Tensor, out: torch.Tensor, offsets: torch.Tensor,
+                        d_bytes: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+    """Enqueue compression of x into the paper-order windowed stream `out` (uint8) and its
+    offset table `offsets` (int64, zvc_window_count + 1 entries)."""
+    n = x.numel()
+    if offsets.numel() < zvc_window_count(n, x.element_size()) + 1:
+        raise ZvcError(ZVC_E_CAPACITY, "zvc_window_compress (offset table too small)")
+    _check(load().zvc_window_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
+                                      offsets.data_ptr(), d_bytes.data_ptr(), ws.data_ptr(),
+                                      ws.numel(), _stream_handle(stream)), "zvc_window_compress")
+
+
+def zvc_window_decompress(comp: torch.Tensor, comp_bytes: int, offsets: torch.Tensor, n: int,
+                          first_window: int, num_windows: int, out: torch.Tensor, stream=None) -> None:
+    """Enqueue decompression of a range of windows into `out` (the elements of those windows)."""
+    w = out.element_size()
+    per = 4096 // w
+    need = max(0, min(n, (first_window + num_windows) * per) - first_window * per)
+    if out.numel() < need:
+        raise ZvcError(ZVC_E_CAPACITY, "zvc_window_decompress (output holds %d elements, %d needed)"
+                       % (out.numel(), need))
+    _check(load().zvc_window_decompress(comp.data_ptr(), comp_bytes, offsets.data_ptr(), n, w,
+                                        first_window, num_windows, out.data_ptr(),
+                                        _stream_handle(stream)), "zvc_window_decompress")
 
 
 def zvc_decompress(comp: torch.Tensor, comp_bytes: int, out: torch.Tensor, ws: torch.Tensor,

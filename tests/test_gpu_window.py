@@ -1,0 +1,130 @@
+"""GPU parity of the paper-order windowed stream (zvc_window_compress /
+zvc_window_decompress) against the CPU oracle, bit for bit, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_1705_01626_amd import workloads, zvc
+from tests.gpu_util import raw_bytes, say
+from tests.test_gpu_parity import random_tensor
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+SIZES = [0, 1, 31, 32, 33, 1023, 1024, 1025, 2047, 2048, 2049, 4096 * 3 + 17, 100003, (1 << 20) + 5,
+         (1 << 24) + 8192 + 77]
+
+
+def window_compress(x, ws=None):
+    n, w = x.numel(), x.element_size()
+    ws = ws if ws is not None else zvc.new_workspace(max(n, 1), w, DEV)
+    comp = zvc.new_compressed_buffer(n, w, DEV)
+    comp.fill_(0xCD)
+    K = zvc.zvc_window_count(n, w)
+    offsets = torch.full((K + 1,), -1, dtype=torch.int64, device=DEV)
+    d_bytes = torch.full((1,), -1, dtype=torch.int64, device=DEV)
+    zvc.zvc_window_compress(x, comp, offsets, d_bytes, ws)
+    torch.cuda.synchronize()
+    return comp, offsets, int(d_bytes.item())
+
+
+def assert_window_parity(x, oracle, label, ws=None, ranges=()):
+    n, w = x.numel(), x.element_size()
+    say("%s n=%d w=%d ptr%%16=%d" % (label, n, w, x.data_ptr() % 16))
+    host = raw_bytes(x)
+    per = 4096 // w
+    expect, expect_offsets = oracle.window_compress(host, w, per)
+    comp, offsets, nbytes = window_compress(x, ws)
+    K = zvc.zvc_window_count(n, w)
+    assert K == oracle.window_count(n, per)
+    assert nbytes == expect.size, "%s: size %d != oracle %d" % (label, nbytes, expect.size)
+    assert offsets.cpu().numpy().astype(np.uint64).tolist() == expect_offsets.tolist(), "%s: offset table" % label
+    assert np.array_equal(comp[:nbytes].cpu().numpy(), expect), "%s: stream bytes differ" % label
+    # whole tensor back
+    out = torch.empty_like(x)
+    out.view(torch.uint8).fill_(0xEE)
+    zvc.zvc_window_decompress(comp, nbytes, offsets, n, 0, K, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(raw_bytes(out), host), "%s: reconstructed tensor differs" % label
+    # ranges of windows, each into a buffer of its own size
+    for first, count in ranges:
+        lo, hi = first * per, min(n, (first + count) * per)
+        part = torch.empty(max(hi - lo, 0), dtype=x.dtype, device=DEV)
+        part.view(torch.uint8).fill_(0x77)
+        zvc.zvc_window_decompress(comp, nbytes, offsets, n, first, count, part)
+        torch.cuda.synchronize()
+        assert np.array_equal(raw_bytes(part), host[lo * w: hi * w]), "%s: windows %d+%d" % (label, first, count)
+        assert np.array_equal(raw_bytes(part), oracle.window_decompress(expect, expect_offsets, n, w, per, first, count))
+    return comp, offsets, nbytes
+
+
+@pytest.mark.parametrize("w", [4, 2])
+@pytest.mark.parametrize("n", SIZES)
+def test_window_sizes_and_densities(oracle, n, w):
+    ws = zvc.new_workspace(max(n, 1), w, DEV)
+    K = zvc.zvc_window_count(n, w)
+    ranges = [(0, 1), (K - 1, 1), (K // 2, min(3, K - K // 2)), (K, 0)] if K > 0 else [(0, 0)]
+    for k, density in enumerate((0.0, 0.35, 1.0)):
+        x = random_tensor(n, w, density, seed=n * 7 + k)
+        assert_window_parity(x, oracle, "window d=%.2f" % density, ws, ranges)
+
+
+@pytest.mark.parametrize("w", [4, 2])
+def test_window_unaligned_pointers(oracle, w):
+    for off, n in ((1, 37), (3, 20011), (5, 4096)):
+        base = random_tensor(n + 16, w, 0.35, seed=n + off)
+        assert_window_parity(base[off: off + n], oracle, "window unaligned off=%d" % off, ranges=[(0, 1)])
+
+
+def test_window_stream_has_the_planar_bytes_count(oracle):
+    """Same size as the planar stream; masks and values inside are the planar ones (checked by the oracle's pins)."""
+    x = workloads.conv_small(seed=5, device=DEV)
+    n, w = x.numel(), 4
+    ws = zvc.new_workspace(n, w, DEV)
+    _, _, nbytes = assert_window_parity(x, oracle, "window conv_small", ws, [(3, 5)])
+    comp = zvc.new_compressed_buffer(n, w, DEV)
+    d_bytes = torch.zeros(1, dtype=torch.int64, device=DEV)
+    zvc.zvc_compress(x, comp, d_bytes, ws)
+    assert int(d_bytes.item()) == nbytes
+
+
+def test_window_decoder_stays_in_bounds_on_damaged_table(oracle):
+    """A table that points past the stream, or claims oversized windows, must not make the
+    kernel read outside the stream: it decodes what is there (zeros beyond)."""
+    n, w = 50000, 4
+    x = random_tensor(n, w, 0.5, seed=99)
+    comp, offsets, nbytes = window_compress(x)
+    K = zvc.zvc_window_count(n, w)
+    bad = offsets.clone()
+    bad[K // 2:] = nbytes + (1 << 40)          # far past the end
+    out = torch.empty_like(x)
+    say("damaged table")
+    zvc.zvc_window_decompress(comp, nbytes, bad, n, 0, K, out)
+    torch.cuda.synchronize()
+    per = 4096 // w
+    good = (K // 2 - 1) * per                   # windows whose both table entries are intact
+    assert torch.equal(out[:good], x[:good])
+    # window K//2 - 1 has a wrong end: clamped to the stream, its own bytes still decode
+    assert torch.equal(out[good: good + per], x[good: good + per])
+    assert not out[(K // 2) * per:].any()
+
+
+def test_window_argument_errors_before_any_launch():
+    x = torch.zeros(5000, dtype=torch.float32, device=DEV)
+    K = zvc.zvc_window_count(5000, 4)
+    comp, offsets, nbytes = window_compress(x)
+    out = torch.empty_like(x)
+    with pytest.raises(zvc.ZvcError):
+        zvc.zvc_window_decompress(comp, nbytes, offsets, 5000, K, 1, out)      # past the last window
+    with pytest.raises(zvc.ZvcError):
+        zvc.zvc_window_decompress(comp, nbytes, offsets, 5000, 0, K + 1, out)
+    small = torch.zeros(K, dtype=torch.int64, device=DEV)
+    with pytest.raises(zvc.ZvcError):
+        zvc.zvc_window_compress(x, comp, small, torch.zeros(1, dtype=torch.int64, device=DEV), zvc.new_workspace(5000, 4, DEV))
+
+
+def test_window_conv1_style_full(oracle):
+    """Full size of the benchmark tensor (297 MB, 72,600 windows)."""
+    x = workloads.conv1_style(seed=0, device=DEV)
+    K = zvc.zvc_window_count(x.numel(), 4)
+    assert K == 72600
+    assert_window_parity(x, oracle, "window conv1_style full", ranges=[(0, 1), (12345, 1000), (K - 2, 2)])
