@@ -6,11 +6,11 @@
 // pipeline beside the memory controllers (section 5.2); this file is a GPU
 // kernel design instead:
 //
-//   * one pass over the input.  A workgroup owns a tile of 16 KB of input; each
-//     lane loads 16 bytes at a time (fully coalesced), tests its elements for a
-//     non-zero bit pattern with integer compares, and the wave derives packed
-//     positions from ballots + mbcnt (the GPU form of the paper's per-sector
-//     prefix sum over mask bits);
+//   * one pass over the input.  A workgroup owns a tile of 16 to 64 KB of input;
+//     each lane loads 16 bytes at a time (fully coalesced), tests its elements
+//     for a non-zero bit pattern with integer compares, and the wave derives
+//     packed positions from ballots + mbcnt (the GPU form of the paper's
+//     per-sector prefix sum over mask bits);
 //   * the offset of a tile's first kept element in the packed stream -- the
 //     paper's "offset to the next mask", a serial chain in hardware -- is a
 //     device-wide exclusive scan of per-tile counts done in the same pass:
@@ -19,9 +19,15 @@
 //   * kept elements are staged by each wave in LDS in packed order and leave as
 //     aligned 16-byte stores; masks leave as one contiguous run per wave.
 //
-// Decompression mirrors it: per-tile popcount of the masks, the same scan, the
-// tile's packed run staged into LDS with aligned 16-byte loads, and every lane
-// rebuilds 16 bytes of output from "bit ? next stored element : zero".
+// Decompression: where a span's stored elements start depends on the masks
+// alone, so a small pre-pass over the masks computes it for every 32 masks; the
+// expand kernel's waves then work independently: each stages its packed run in
+// LDS with aligned 16-byte loads and rebuilds 16 bytes of output per lane from
+// "bit ? next stored element : zero".
+//
+// Two variants share these kernels: a fused ReLU + ZVC encoder (pre-activations
+// in, stream of ReLU(x) out) and the paper's own stream order ("mask, then its
+// non-zeros") in independently decodable 4 KB windows with an offset table.
 
 #include "zvc.h"
 
