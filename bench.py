@@ -81,7 +81,7 @@ def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool 
     while reps < 1 or (spent < budget_s and reps < 50):
         t0 = time.perf_counter()
         if windowed:
-            per = 4096 // w
+            per = 1024 // w
             windows = (n + per - 1) // per
             offsets = np.zeros(windows + 1, dtype=np.uint64)
             lib.zvc_ref_window_compress(vp(host_bytes.ctypes.data), n, w, per, vp(comp.ctypes.data),
@@ -288,7 +288,7 @@ def main() -> int:
     if args.windowed:
         windows = zvc.zvc_window_count(n, w)
         offsets = torch.zeros(windows + 1, dtype=torch.int64, device=dev)
-        described += "; paper-order stream in 4 KB windows with an offset table"
+        described += "; paper-order stream in 1 KB windows with an offset table"
 
         def encode(t, c, b, s):
             zvc.zvc_window_compress(t, c, offsets, b, s)

@@ -155,18 +155,20 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
 /* ---- the paper's own stream order, in independently decodable windows ------ */
 
 /* Section 5.1 appends a group's non-zero elements right after its mask, and the
- * DMA engine of section 6 works on windows of 4 KB of uncompressed data.  The
- * windowed stream is that order: window after window (4096 / w elements each,
+ * DMA engine of section 6 works on windows of uncompressed data, each decodable
+ * on its own (4 KB there; the window size does not change the stream's bytes).
+ * The windowed stream is that order: window after window (1024 / w elements
+ * each -- 1 KB, so that four lanes of a wave can each walk one window's masks --
  * the last one possibly shorter), inside a window group after group, for each
  * group its 32-bit mask (little-endian; for w = 2 it may fall on a 2-byte
  * boundary) and then its kept elements.  Windows are packed back to back, so
  * the stream has exactly the bytes of the planar one, 4*ceil(n/32) + w*nnz.
  * Beside it goes a table of zvc_window_count(n, w) + 1 byte offsets: window k
  * occupies [offsets[k], offsets[k+1]) and the last entry is the stream's size.
- * The table (this library's addition, not counted in the compressed size)
- * makes any range of windows decodable without touching the rest. */
+ * The table (this library's addition, not counted in the compressed size: 8
+ * bytes per KB) makes any range of windows decodable without touching the rest. */
 
-/* Number of windows for n elements of width w: ceil(n*w / 4096).  0 for a bad w. */
+/* Number of windows for n elements of width w: ceil(n*w / 1024).  0 for a bad w. */
 size_t zvc_window_count(size_t n, int w);
 
 /* Compress into the windowed stream.  d_out / out_cap / d_bytes / workspace as
@@ -180,7 +182,7 @@ zvc_status zvc_window_compress(const void* d_in, size_t n, int w, void* d_out, s
  * windowed stream of n elements (a partial prefetch).  d_stream points at the
  * START of the stream (aligned to w) and stream_bytes is the number of readable
  * bytes there; d_offsets is the whole table.  d_out receives the elements of
- * those windows only, i.e. it points at where element first_window * 4096 / w
+ * those windows only, i.e. it points at where element first_window * 1024 / w
  * of the tensor goes.  Needs no workspace.  The kernel reads nothing outside
  * [d_stream, d_stream + stream_bytes) and the table entries of the windows
  * asked for; what a damaged table or mask asks for beyond a window's bytes

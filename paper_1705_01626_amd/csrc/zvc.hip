@@ -544,14 +544,14 @@ __device__ __forceinline__ void load_tile(uint4 (&data)[LOADS], const EncoderArg
 // ReLU(input): the dense ReLU output is never written or read.
 //
 // WINDOWED selects the paper's own stream order (section 5.1: a group's
-// non-zeros are appended right after its mask) in windows of 4 KB of input
-// (section 6), packed back to back, plus a table with the byte offset of every
-// window.  A window is what one wave stages at a time (4 loads), so the only
-// differences are where things go in the wave's LDS slice -- the mask of group
-// g of the window sits before the group's elements, i.e. after g masks and all
-// earlier kept elements -- and that masks leave with the values instead of going
-// to a mask area.  The scan is the same: a window's byte offset is 4 x (groups
-// before it) + W x (kept elements before it).
+// non-zeros are appended right after its mask) in windows of 1 KB of input,
+// packed back to back, plus a table with the byte offset of every window.  A
+// window is one load of a wave and a wave stages four of them at a time, so the
+// only differences are where things go in the wave's LDS slice -- the mask of
+// group g of the step sits before the group's elements, i.e. after g masks and
+// all earlier kept elements -- and that masks leave with the values instead of
+// going to a mask area.  The scan is the same: a window's byte offset is
+// 4 x (groups before it) + W x (kept elements before it).
 template <int W, int LOADS, bool ALIGNED, bool RELU, bool WINDOWED>
 __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     using G = Geometry<W, LOADS>;
@@ -559,7 +559,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     constexpr int LPG = G::kLanesPerGroup;
     constexpr int kStepGroups = G::kEncStageLoads * G::kGroupsPerLoad;   // masks of one window: 32 | 64
     constexpr int kMaskUnits = 4 / W;                                    // a mask in units of W bytes
-    static_assert(!WINDOWED || G::kEncStageLoads == 4, "a window is four loads of a wave (4 KB)");
+    static_assert(!WINDOWED || G::kEncStageLoads == kStageLoads, "the windowed decoder expands four windows per wave");
 
     __shared__ __align__(16) unsigned char
         s_stage[kWaves][G::kEncWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0)];
@@ -662,9 +662,9 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     for (int h = 0; h < G::kEncStageSteps; ++h) {
         const unsigned first_rank = run[h * G::kEncStageLoads];
         const unsigned step_total = run[(h + 1) * G::kEncStageLoads] - first_rank;
-        // windowed: the step is window `window`, whose groups may end with the tensor
-        const size_t window = (static_cast<size_t>(tile) * kWaves + wave) * G::kEncStageSteps + h;
-        const size_t window_group0 = window * kStepGroups;
+        // windowed: the step is four windows (one per load), whose groups may end with the tensor
+        const size_t step = (static_cast<size_t>(tile) * kWaves + wave) * G::kEncStageSteps + h;
+        const size_t window_group0 = step * kStepGroups;
         const unsigned valid_groups =
             !WINDOWED || window_group0 >= a.num_groups ? 0u
             : a.num_groups - window_group0 < kStepGroups ? static_cast<unsigned>(a.num_groups - window_group0)
@@ -673,8 +673,15 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W +   // wave-uniform
                              (WINDOWED ? 4 * (window_group0 < a.num_groups ? window_group0 : a.num_groups) : 0);
         const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
-        if (WINDOWED && valid_groups != 0 && lane == 0)
-            a.offsets[window] = static_cast<unsigned long long>(dst - a.values);
+        if (WINDOWED && lane == 0) {
+            // the byte offset of every window that exists: its masks before it, its kept elements before it
+#pragma unroll
+            for (int jj = 0; jj < G::kEncStageLoads; ++jj)
+                if (static_cast<unsigned>(jj * G::kGroupsPerLoad) < valid_groups)
+                    a.offsets[step * G::kEncStageLoads + jj] =
+                        static_cast<unsigned long long>(dst - a.values) + 4u * jj * G::kGroupsPerLoad +
+                        W * (run[h * G::kEncStageLoads + jj] - first_rank);
+        }
 #pragma unroll
         for (int jj = 0; jj < G::kEncStageLoads; ++jj) {
             const int j = h * G::kEncStageLoads + jj;
@@ -722,7 +729,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         const unsigned long long total =
             4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
         *a.d_bytes = total;
-        if (WINDOWED) a.offsets[div_up(a.num_groups, kStepGroups)] = total;
+        if (WINDOWED) a.offsets[div_up(a.num_groups, G::kGroupsPerLoad)] = total;
     }
 
     if (tile == a.num_tiles - 1 && wave == 0)
@@ -992,17 +999,18 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     }
 }
 
-// Decoder of the windowed stream.  One wave per window, no scan and no
-// pre-pass: the offset table says where a window's bytes are, and a window
-// decodes from its own bytes alone (section 5.2: the popcount of a mask gives
-// the offset of the next mask).  The wave stages the window's bytes in LDS,
-// lane 0 walks the masks one after the other -- the serial chain the paper's
-// decoder has too, here at most 64 steps through LDS -- and leaves every
-// mask and the position of its first element for the other lanes, which then
-// rebuild 16 bytes of output per load as in the planar decoder.  Reads stay
-// inside [0, stream_bytes) and inside the staged window whatever the table and
-// the masks say; what a damaged stream asks for beyond that decodes as zero.
-constexpr int kWindowBytes = 4096;      // uncompressed bytes per window (section 6)
+// Decoder of the windowed stream.  No scan and no pre-pass: the offset table
+// says where a window's bytes are, and a window decodes from its own bytes alone
+// (section 5.2: the popcount of a mask gives the offset of the next mask).  A
+// wave takes four consecutive windows (4 KB of output): it stages their bytes
+// in LDS, lanes 0..3 each walk the masks of one window one after the other --
+// the serial chain the paper's decoder has too, here 8 or 16 steps through LDS
+// -- and leave every mask and the position of its first element for the other
+// lanes, which then rebuild 16 bytes of output per load as in the planar
+// decoder.  Reads stay inside [0, stream_bytes) and inside the staged bytes
+// whatever the table and the masks say; what a damaged stream asks for beyond
+// that decodes as zero.
+constexpr int kWindowBytes = 1024;      // uncompressed bytes per window: one load of a wave
 
 template <int W, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void window_decode_kernel(
@@ -1011,11 +1019,11 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     size_t first_window, size_t num_windows, unsigned char* __restrict__ out) {
     constexpr int E = 16 / W;
     constexpr int LPG = 32 / E;
-    constexpr int GPL = kWaveSize / LPG;
-    constexpr int kStepGroups = kStageLoads * GPL;          // masks per window: 32 | 64
-    constexpr int kWindowElems = kStepGroups * 32;
-    constexpr unsigned kMaxBytes = kWindowBytes + 4 * kStepGroups;
-    static_assert(kWindowElems * W == kWindowBytes, "a window is one staging step of a wave");
+    constexpr int GPL = kWaveSize / LPG;                    // masks per window: 8 | 16
+    constexpr int kStepGroups = kStageLoads * GPL;          // masks per wave: 32 | 64
+    constexpr int kWindowElems = GPL * 32;
+    constexpr unsigned kMaxBytes = kStageLoads * (kWindowBytes + 4 * GPL);
+    static_assert(kWindowElems * W == kWindowBytes, "a window is one load of a wave");
 
     __shared__ __align__(16) unsigned char s_stage[kWaves][kMaxBytes + 16];
     __shared__ unsigned s_mask[kWaves][kStepGroups];
@@ -1024,18 +1032,19 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
-    const size_t local = static_cast<size_t>(blockIdx.x) * kWaves + wave;
+    const size_t local = (static_cast<size_t>(blockIdx.x) * kWaves + wave) * kStageLoads;   // first of the wave's windows
     if (local >= num_windows) return;
-    const size_t window = first_window + local;
-    const size_t group0 = window * kStepGroups;
-    const unsigned valid_groups = group0 >= num_groups ? 0u
-        : num_groups - group0 < kStepGroups ? static_cast<unsigned>(num_groups - group0)
-                                            : static_cast<unsigned>(kStepGroups);
+    const size_t window0 = first_window + local;
+    const unsigned windows_here =
+        num_windows - local < kStageLoads ? static_cast<unsigned>(num_windows - local) : kStageLoads;
 
-    // ---- the window's bytes, clamped to what can be there
-    unsigned long long lo = offsets[window], hi = offsets[window + 1];
-    if (lo > stream_bytes) lo = stream_bytes;
-    if (hi > stream_bytes) hi = stream_bytes;
+    // ---- the windows' bytes, clamped to what can be there
+    const auto clamped = [&](size_t k) {
+        const unsigned long long o = offsets[k];
+        return o > stream_bytes ? stream_bytes : o;
+    };
+    const unsigned long long lo = clamped(window0);
+    unsigned long long hi = clamped(window0 + windows_here);
     if (hi < lo) hi = lo;
     const unsigned bytes = hi - lo > kMaxBytes ? kMaxBytes : static_cast<unsigned>(hi - lo);
     const unsigned char* src = stream + lo;    // wave-uniform, aligned to W
@@ -1045,10 +1054,19 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     wave_copy_in<W>(stage, src - shift, shift, limit, limit, lane);
     wave_lds_sync();
 
-    // ---- the serial walk over the masks
-    if (lane == 0) {
-        unsigned p = shift;
-        for (unsigned g = 0; g < static_cast<unsigned>(kStepGroups); ++g) {
+    // ---- lanes 0..3: the serial walk over one window's masks each
+    if (lane < kStageLoads) {
+        const size_t window = window0 + lane;
+        const size_t group0 = window * GPL;
+        const unsigned valid_groups = static_cast<unsigned>(lane) >= windows_here || group0 >= num_groups ? 0u
+            : num_groups - group0 < GPL ? static_cast<unsigned>(num_groups - group0)
+                                        : static_cast<unsigned>(GPL);
+        unsigned p = limit;   // a window that is not there, or whose offset is off, reads nothing
+        if (valid_groups != 0) {
+            const unsigned long long o = clamped(window);
+            if (o >= lo && o - lo <= bytes) p = shift + static_cast<unsigned>(o - lo);
+        }
+        for (unsigned g = 0; g < static_cast<unsigned>(GPL); ++g) {
             unsigned m = 0;
             if (g < valid_groups && p + 4u <= limit) {
                 if (W == 4)
@@ -1057,20 +1075,21 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
                     m = *reinterpret_cast<const unsigned short*>(stage + p) |
                         (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(stage + p + 2)) << 16);
             }
-            s_mask[wave][g] = m;
-            s_first[wave][g] = p + 4u;
+            s_mask[wave][lane * GPL + g] = m;
+            s_first[wave][lane * GPL + g] = p + 4u;
             p += 4u + W * __popc(m);
         }
     }
     wave_lds_sync();
 
-    // ---- expand
-    const size_t window_elem0 = window * kWindowElems;           // in the tensor
-    unsigned char* wout = out + local * kWindowBytes;            // this window's output
-    const bool full = ALIGNED && window_elem0 + kWindowElems <= n;
+    // ---- expand: load jj is window jj of the wave
+    const size_t elem0 = window0 * kWindowElems;                  // in the tensor
+    unsigned char* wout = out + local * kWindowBytes;             // these windows' output
+    const bool full = ALIGNED && windows_here == kStageLoads && elem0 + kStageLoads * kWindowElems <= n;
 #pragma unroll
     for (int jj = 0; jj < kStageLoads; ++jj) {
-        const unsigned in_window = static_cast<unsigned>((jj * kWaveSize + lane) * E);   // element within the window
+        if (static_cast<unsigned>(jj) >= windows_here) break;
+        const unsigned in_step = static_cast<unsigned>((jj * kWaveSize + lane) * E);   // element within the wave's part
         const int gl = jj * GPL + lane / LPG;
         const unsigned gm = s_mask[wave][gl];
         const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
@@ -1090,17 +1109,17 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
             }
             at += ((field >> c) & 1u) ? W : 0;
         }
-        const size_t e0 = window_elem0 + in_window;
+        const size_t e0 = elem0 + in_step;
         if (full || (ALIGNED && e0 + E <= n)) {
-            store16_stream(wout + in_window * W, make_uint4(d[0], d[1], d[2], d[3]));
+            store16_stream(wout + in_step * W, make_uint4(d[0], d[1], d[2], d[3]));
         } else {
 #pragma unroll
             for (int c = 0; c < E; ++c) {
                 if (e0 + c < n) {
                     if (W == 4)
-                        reinterpret_cast<unsigned*>(wout)[in_window + c] = d[c];
+                        reinterpret_cast<unsigned*>(wout)[in_step + c] = d[c];
                     else
-                        reinterpret_cast<unsigned short*>(wout)[in_window + c] = static_cast<unsigned short>(
+                        reinterpret_cast<unsigned short*>(wout)[in_step + c] = static_cast<unsigned short>(
                             (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
                 }
             }
@@ -1501,7 +1520,7 @@ zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, cons
                                  ? (first_window + num_windows) * elems_per_window : n;
     const size_t out_bytes = (last_elem - first_window * elems_per_window) * static_cast<size_t>(w);
     if (ranges_overlap(d_stream, stream_bytes, d_out, out_bytes)) return ZVC_E_ARG;
-    const size_t blocks = div_up(num_windows, kWaves);
+    const size_t blocks = div_up(num_windows, static_cast<size_t>(kWaves) * kStageLoads);
     if (blocks > 0x7FFFFFFFull) return ZVC_E_ARG;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const unsigned char* in = static_cast<const unsigned char*>(d_stream);

@@ -201,7 +201,7 @@ def zvc_window_decompress(comp: torch.Tensor, comp_bytes: int, offsets: torch.Te
                           first_window: int, num_windows: int, out: torch.Tensor, stream=None) -> None:
     """Enqueue decompression of a range of windows into `out` (the elements of those windows)."""
     w = out.element_size()
-    per = 4096 // w
+    per = 1024 // w
     need = max(0, min(n, (first_window + num_windows) * per) - first_window * per)
     if out.numel() < need:
         raise ZvcError(ZVC_E_CAPACITY, "zvc_window_decompress (output holds %d elements, %d needed)"

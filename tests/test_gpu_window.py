@@ -31,7 +31,7 @@ def assert_window_parity(x, oracle, label, ws=None, ranges=()):
     n, w = x.numel(), x.element_size()
     say("%s n=%d w=%d ptr%%16=%d" % (label, n, w, x.data_ptr() % 16))
     host = raw_bytes(x)
-    per = 4096 // w
+    per = 1024 // w
     expect, expect_offsets = oracle.window_compress(host, w, per)
     comp, offsets, nbytes = window_compress(x, ws)
     K = zvc.zvc_window_count(n, w)
@@ -100,7 +100,7 @@ def test_window_decoder_stays_in_bounds_on_damaged_table(oracle):
     say("damaged table")
     zvc.zvc_window_decompress(comp, nbytes, bad, n, 0, K, out)
     torch.cuda.synchronize()
-    per = 4096 // w
+    per = 1024 // w
     good = (K // 2 - 1) * per                   # windows whose both table entries are intact
     assert torch.equal(out[:good], x[:good])
     # window K//2 - 1 has a wrong end: clamped to the stream, its own bytes still decode
@@ -123,8 +123,8 @@ def test_window_argument_errors_before_any_launch():
 
 
 def test_window_conv1_style_full(oracle):
-    """Full size of the benchmark tensor (297 MB, 72,600 windows)."""
+    """Full size of the benchmark tensor (297 MB, 290,400 windows)."""
     x = workloads.conv1_style(seed=0, device=DEV)
     K = zvc.zvc_window_count(x.numel(), 4)
-    assert K == 72600
+    assert K == 290400
     assert_window_parity(x, oracle, "window conv1_style full", ranges=[(0, 1), (12345, 1000), (K - 2, 2)])
