@@ -603,8 +603,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         asm volatile("" : "+v"(below16[j / 2]), "+s"(load_total));
         run[j + 1] = run[j] + load_total;
         // the group's mask: OR of the lanes' bit fields, each at its position
-        const unsigned m = group_or<LPG>(bits << field_shift);
-        if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
+        // (the windowed layout forms it again when it stages the load: keeping
+        // it in registers through the scan costs the 64 KB tile a wave of occupancy)
+        if (!WINDOWED) {
+            const unsigned m = group_or<LPG>(bits << field_shift);
+            if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
+        }
         __builtin_amdgcn_sched_barrier(0);
         if (j == 0) ZVC_TRACE_POINT(tile, 1);
     }
@@ -689,31 +693,31 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
             const unsigned rank0 = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
             const unsigned group = static_cast<unsigned>(jj * G::kGroupsPerLoad + lane / LPG);
             unsigned char* at = stage + shift + W * (rank0 + (WINDOWED ? kMaskUnits * (group + 1u) : 0u));
-            if (WINDOWED) {
-                // the lane that kept this load's mask puts it before the group's elements,
-                // whose first rank the group's first lane knows
-                const unsigned group_rank0 = __shfl(rank0, lane - lane_in_group);
-                if (lane_in_group == j % LPG && group < valid_groups) {
-                    unsigned char* mask_at = stage + shift + W * (group_rank0 + kMaskUnits * group);
-                    const unsigned m = my_mask[j / LPG];
-                    if (W == 4) {
-                        *reinterpret_cast<unsigned*>(mask_at) = m;
-                    } else {
-                        *reinterpret_cast<unsigned short*>(mask_at) = static_cast<unsigned short>(m);
-                        *reinterpret_cast<unsigned short*>(mask_at + 2) = static_cast<unsigned short>(m >> 16);
-                    }
-                }
-            }
+            unsigned bits = 0;
 #pragma unroll
             for (int c = 0; c < E; ++c) {
                 const bool nz = element_kept<W, RELU>(cur[j], c);
                 const unsigned v = element_of<W>(cur[j], c);
+                bits |= (nz ? 1u : 0u) << c;
                 if (__builtin_expect(nz, 1)) {   // predicated: write and advance in the kept lanes only
                     if (W == 4)
                         *reinterpret_cast<unsigned*>(at) = v;
                     else
                         *reinterpret_cast<unsigned short*>(at) = static_cast<unsigned short>(v);
                     at += W;
+                }
+            }
+            if (WINDOWED) {
+                // the group's first lane puts the mask before the group's elements
+                const unsigned m = group_or<LPG>(bits << field_shift);
+                if (lane_in_group == 0 && group < valid_groups) {
+                    unsigned char* mask_at = stage + shift + W * (rank0 + kMaskUnits * group);
+                    if (W == 4) {
+                        *reinterpret_cast<unsigned*>(mask_at) = m;
+                    } else {
+                        *reinterpret_cast<unsigned short*>(mask_at) = static_cast<unsigned short>(m);
+                        *reinterpret_cast<unsigned short*>(mask_at + 2) = static_cast<unsigned short>(m >> 16);
+                    }
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
