@@ -256,3 +256,21 @@ def test_decoder_many_chunks_and_reuse(oracle):
     for n in (4096 * 32, 4096 * 32 + 1, 4096 * 32 * 2 - 1, n_max, 4096 * 32 * 7 + 31, 1000):
         x = random_tensor(n, w, 0.41, seed=n)
         assert_parity(x, oracle, "pre-pass chunks n=%d" % n, ws=ws)
+
+
+def test_decoder_survives_garbage_stream(oracle):
+    """Random bytes as a compressed stream: masks then claim any number of stored elements, but
+    reads are clamped to comp_bytes and a step never stages more than it has room for, so the
+    kernels finish normally; the workspace stays usable."""
+    for w, n in ((4, 700001), (2, 1300003)):
+        g = torch.Generator(device="cpu").manual_seed(n)
+        cap = zvc.zvc_max_compressed_bytes(n, w)
+        junk = torch.randint(0, 256, (cap,), generator=g, dtype=torch.uint8).to(DEV)
+        ws = zvc.new_workspace(n, w, DEV)
+        out = torch.empty(n, dtype=DTYPES[w], device=DEV)
+        for comp_bytes in (cap, 4 * ((n + 31) // 32), 4 * ((n + 31) // 32) + w * (n // 3)):
+            say("garbage stream w=%d comp_bytes=%d" % (w, comp_bytes))
+            zvc.zvc_decompress(junk, comp_bytes, out, ws)
+            torch.cuda.synchronize()
+        x = random_tensor(n, w, 0.4, seed=1)
+        assert_parity(x, oracle, "after garbage", ws)

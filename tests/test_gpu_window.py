@@ -128,3 +128,30 @@ def test_window_conv1_style_full(oracle):
     K = zvc.zvc_window_count(x.numel(), 4)
     assert K == 290400
     assert_window_parity(x, oracle, "window conv1_style full", ranges=[(0, 1), (12345, 1000), (K - 2, 2)])
+
+
+def test_window_decoder_survives_garbage_stream_and_table():
+    """Random bytes as the stream (with a genuine table) and random numbers as the table (with a
+    genuine stream): every read is clamped to the stream and to the staged bytes, so the kernel
+    finishes normally whatever it decodes.  Then a genuine call must still work."""
+    n, w = 300000, 4
+    x = random_tensor(n, w, 0.5, seed=4)
+    comp, offsets, nbytes = window_compress(x)
+    K = zvc.zvc_window_count(n, w)
+    g = torch.Generator(device="cpu").manual_seed(8)
+    junk = torch.randint(0, 256, (comp.numel(),), generator=g, dtype=torch.uint8).to(DEV)
+    out = torch.empty_like(x)
+    say("garbage stream")
+    zvc.zvc_window_decompress(junk, nbytes, offsets, n, 0, K, out)
+    torch.cuda.synchronize()
+    wild = torch.randint(0, 1 << 62, (K + 1,), generator=g, dtype=torch.int64).to(DEV)
+    say("garbage table")
+    zvc.zvc_window_decompress(comp, nbytes, wild, n, 0, K, out)
+    torch.cuda.synchronize()
+    wild_small = torch.randint(0, nbytes, (K + 1,), generator=g, dtype=torch.int64).to(DEV)
+    say("garbage table inside the stream")
+    zvc.zvc_window_decompress(comp, nbytes, wild_small, n, 0, K, out)
+    torch.cuda.synchronize()
+    zvc.zvc_window_decompress(comp, nbytes, offsets, n, 0, K, out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, x)
