@@ -43,7 +43,7 @@ namespace {
 constexpr int kThreads = 256;                 // 4 waves of 64 lanes
 constexpr int kWaveSize = 64;
 constexpr int kWaves = kThreads / kWaveSize;
-constexpr int kFinishLanes = 64;              // finish counters, one 128-byte line each
+constexpr int kFinishLanes = 64;              // arrival counters, one 128-byte line each
 constexpr size_t kHeaderBytes = 256 + 128 * (kFinishLanes + 1);  // header, then the scan state
 constexpr int kMinLoads = 4;                  // smallest tile: 16 KB (sizes the workspace)
 constexpr int kStageLoads = 4;                // 16-byte loads a wave stages through LDS at a time
@@ -64,8 +64,6 @@ struct Geometry {
     static constexpr int kTileGroups = kTileElems / 32;
     // mask hand-off: load j's mask is kept by lane (j % kLanesPerGroup) of the group
     static constexpr int kMaskRegs = (LOADS + kLanesPerGroup - 1) / kLanesPerGroup;
-    // decoder: masks handled per thread
-    static constexpr int kMasksPerThread = kTileGroups > kThreads ? kTileGroups / kThreads : 1;
     // per-wave LDS staging buffer: kStageLoads wave-loads plus alignment slack
     static constexpr int kStageSteps = LOADS / kStageLoads;
     // (16 bytes so the slice can mirror the destination's alignment)
@@ -81,7 +79,7 @@ struct Geometry {
 struct WsHeader {
     unsigned long long pad0[2];
     unsigned long long size_word;  // compressed size for zvc_offload's read-back
-    unsigned long long helped;     // predecessor counts computed by a waiting tile (last encoder call)
+    unsigned long long helped;     // predecessor counts computed by a waiting tile since the workspace's init
     unsigned long long pad[28];
     // Arrival counters, shared by the encoder and the decoder's pre-pass (calls
     // on one workspace do not overlap).  Encoder: tile t counts itself finished
@@ -92,7 +90,11 @@ struct WsHeader {
     // the last.  Count-only pass: the same, with `sum` collecting the counts.
     // One counter per 128-byte line keeps the atomics on one address (about
     // 11 ns each) far apart in time.
-    struct alignas(128) Line { unsigned value; unsigned pad; unsigned long long sum; } finish[kFinishLanes], finish_top;
+    struct alignas(128) Line {
+        unsigned value;
+        unsigned pad;
+        unsigned long long sum;
+    } finish[kFinishLanes], finish_top;
 };
 static_assert(sizeof(WsHeader) == kHeaderBytes, "header size");
 
