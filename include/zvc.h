@@ -204,6 +204,13 @@ zvc_status zvc_offload(const void* d_in, size_t n, int w, void* d_stage, size_t 
                        void* h_pinned, size_t h_cap, uint64_t* h_bytes, void* d_ws, size_t ws,
                        hipStream_t compute, hipStream_t copy);
 
+/* zvc_offload with the fused ReLU encoder: d_in holds pre-activations, the host
+ * receives the stream of ReLU(d_in) (see zvc_relu_compress).  zvc_prefetch
+ * brings back ReLU(d_in). */
+zvc_status zvc_relu_offload(const void* d_in, size_t n, int w, void* d_stage, size_t stage_cap,
+                            void* h_pinned, size_t h_cap, uint64_t* h_bytes, void* d_ws, size_t ws,
+                            hipStream_t compute, hipStream_t copy);
+
 /* Prefetch, the mirror of zvc_offload: enqueues the host-to-device copy of
  * `bytes` bytes from h_pinned into d_stage on `copy`, then the decompression
  * into d_out on `compute`, ordered after the copy.  No host wait. */

@@ -1377,6 +1377,38 @@ zvc_status compress_impl(Encoder mode, const void* d_in, size_t n, int w, void* 
     return hip_ok(hipGetLastError());
 }
 
+zvc_status offload_impl(Encoder mode, const void* d_in, size_t n, int w, void* d_stage,
+                        size_t stage_cap, void* h_pinned, size_t h_cap, uint64_t* h_bytes, void* d_ws,
+                        size_t ws, hipStream_t compute, hipStream_t copy) {
+    if (w != 2 && w != 4) return ZVC_E_WIDTH;
+    if (h_bytes == nullptr || (h_pinned == nullptr && n != 0)) return ZVC_E_ARG;
+    if (h_cap < zvc_max_compressed_bytes(n, w)) return ZVC_E_CAPACITY;
+    if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
+    WsHeader* hdr = static_cast<WsHeader*>(d_ws);
+    uint64_t* d_size = reinterpret_cast<uint64_t*>(&hdr->size_word);
+    // the size word sits in the header and survives until the next offload on this workspace
+    if (zvc_status st = compress_impl(mode, d_in, n, w, d_stage, stage_cap, d_size, nullptr, d_ws, ws,
+                                      compute))
+        return st;
+    if (hipMemcpyAsync(h_bytes, d_size, 8, hipMemcpyDeviceToHost, compute) != hipSuccess)
+        return ZVC_E_HIP;
+    hipEvent_t ev;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return ZVC_E_HIP;
+    zvc_status st = ZVC_OK;
+    if (hipEventRecord(ev, compute) != hipSuccess || hipEventSynchronize(ev) != hipSuccess) {
+        st = ZVC_E_HIP;
+    } else if (*h_bytes > h_cap) {
+        st = ZVC_E_CAPACITY;
+    } else if (*h_bytes != 0) {
+        if (copy != compute && hipStreamWaitEvent(copy, ev, 0) != hipSuccess) st = ZVC_E_HIP;
+        if (st == ZVC_OK && hipMemcpyAsync(h_pinned, d_stage, *h_bytes, hipMemcpyDeviceToHost,
+                                           copy) != hipSuccess)
+            st = ZVC_E_HIP;
+    }
+    (void)hipEventDestroy(ev);
+    return st;
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------ C ABI
@@ -1581,33 +1613,15 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
 zvc_status zvc_offload(const void* d_in, size_t n, int w, void* d_stage, size_t stage_cap,
                        void* h_pinned, size_t h_cap, uint64_t* h_bytes, void* d_ws, size_t ws,
                        hipStream_t compute, hipStream_t copy) {
-    if (w != 2 && w != 4) return ZVC_E_WIDTH;
-    if (h_bytes == nullptr || (h_pinned == nullptr && n != 0)) return ZVC_E_ARG;
-    if (h_cap < zvc_max_compressed_bytes(n, w)) return ZVC_E_CAPACITY;
-    if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
-    WsHeader* hdr = static_cast<WsHeader*>(d_ws);
-    uint64_t* d_size = reinterpret_cast<uint64_t*>(&hdr->size_word);
-    // the size word sits in the header; zvc_compress's reset runs before the
-    // kernel that writes it, so it survives until the next call on this workspace
-    if (zvc_status st = zvc_compress(d_in, n, w, d_stage, stage_cap, d_size, d_ws, ws, compute))
-        return st;
-    if (hipMemcpyAsync(h_bytes, d_size, 8, hipMemcpyDeviceToHost, compute) != hipSuccess)
-        return ZVC_E_HIP;
-    hipEvent_t ev;
-    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return ZVC_E_HIP;
-    zvc_status st = ZVC_OK;
-    if (hipEventRecord(ev, compute) != hipSuccess || hipEventSynchronize(ev) != hipSuccess) {
-        st = ZVC_E_HIP;
-    } else if (*h_bytes > h_cap) {
-        st = ZVC_E_CAPACITY;
-    } else if (*h_bytes != 0) {
-        if (copy != compute && hipStreamWaitEvent(copy, ev, 0) != hipSuccess) st = ZVC_E_HIP;
-        if (st == ZVC_OK && hipMemcpyAsync(h_pinned, d_stage, *h_bytes, hipMemcpyDeviceToHost,
-                                           copy) != hipSuccess)
-            st = ZVC_E_HIP;
-    }
-    (void)hipEventDestroy(ev);
-    return st;
+    return offload_impl(Encoder::kPlain, d_in, n, w, d_stage, stage_cap, h_pinned, h_cap, h_bytes, d_ws,
+                        ws, compute, copy);
+}
+
+zvc_status zvc_relu_offload(const void* d_in, size_t n, int w, void* d_stage, size_t stage_cap,
+                            void* h_pinned, size_t h_cap, uint64_t* h_bytes, void* d_ws, size_t ws,
+                            hipStream_t compute, hipStream_t copy) {
+    return offload_impl(Encoder::kRelu, d_in, n, w, d_stage, stage_cap, h_pinned, h_cap, h_bytes, d_ws,
+                        ws, compute, copy);
 }
 
 zvc_status zvc_prefetch(const void* h_pinned, uint64_t bytes, size_t n, int w, void* d_stage,

@@ -26,7 +26,7 @@ EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
            "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
-           "zvc_relu_compress", "zvc_window_count", "zvc_window_compress", "zvc_window_decompress")
+           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_compress", "zvc_window_decompress")
 
 _lib = None
 
@@ -76,6 +76,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_decompress.argtypes = [vp, sz, sz, ci, vp, vp, sz, vp]
     lib.zvc_offload.restype = ci
     lib.zvc_offload.argtypes = [vp, sz, ci, vp, sz, vp, sz, vp, vp, sz, vp, vp]
+    lib.zvc_relu_offload.restype = ci
+    lib.zvc_relu_offload.argtypes = [vp, sz, ci, vp, sz, vp, sz, vp, vp, sz, vp, vp]
     lib.zvc_prefetch.restype = ci
     lib.zvc_prefetch.argtypes = [vp, u64, sz, ci, vp, sz, vp, vp, sz, vp, vp]
     lib.zvc_set_lookback_patience.restype = None
@@ -229,6 +231,18 @@ def zvc_offload(x: torch.Tensor, stage: torch.Tensor, h_pinned: torch.Tensor,
                               stage.numel(), h_pinned.data_ptr(), h_pinned.numel(),
                               h_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
                               _stream_handle(compute), _stream_handle(copy)), "zvc_offload")
+    return int(h_bytes.item())
+
+
+def zvc_relu_offload(x: torch.Tensor, stage: torch.Tensor, h_pinned: torch.Tensor,
+                     h_bytes: torch.Tensor, ws: torch.Tensor, compute: torch.cuda.Stream,
+                     copy: torch.cuda.Stream) -> int:
+    """zvc_offload with the fused ReLU encoder: x holds pre-activations, the host gets the
+    stream of ReLU(x)."""
+    _check(load().zvc_relu_offload(x.data_ptr(), x.numel(), x.element_size(), stage.data_ptr(),
+                                   stage.numel(), h_pinned.data_ptr(), h_pinned.numel(),
+                                   h_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
+                                   _stream_handle(compute), _stream_handle(copy)), "zvc_relu_offload")
     return int(h_bytes.item())
 
 

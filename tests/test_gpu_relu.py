@@ -108,3 +108,30 @@ def test_relu_conv1_style_full(oracle):
     n = pre.numel()
     d = (nbytes - n // 8) / 4 / n
     assert 0.45 < d < 0.56
+
+
+def test_relu_offload_and_prefetch(oracle):
+    """Pre-activations leave the GPU as the stream of their ReLU and come back as ReLU(x)."""
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    for dtype in (torch.float32, torch.bfloat16):
+        post = workloads.conv_small(seed=6, device=DEV)
+        pre = workloads.pre_activation(post, seed=7).to(dtype)
+        n, w = pre.numel(), pre.element_size()
+        cap = zvc.zvc_max_compressed_bytes(n, w)
+        stage = torch.empty(cap, dtype=torch.uint8, device=DEV)
+        h_pinned = torch.empty(cap, dtype=torch.uint8, pin_memory=True)
+        h_bytes = torch.zeros(1, dtype=torch.int64, pin_memory=True)
+        ws = zvc.new_workspace(n, w, DEV)
+        torch.cuda.synchronize()
+        say("relu offload %s" % dtype)
+        nbytes = zvc.zvc_relu_offload(pre, stage, h_pinned, h_bytes, ws, compute, copy)
+        copy.synchronize()
+        expect = oracle.relu_compress_stream(raw_bytes(pre), w)
+        assert nbytes == expect.size
+        assert np.array_equal(h_pinned[:nbytes].numpy(), expect)
+        stage.zero_()
+        out = torch.empty_like(pre)
+        torch.cuda.synchronize()
+        zvc.zvc_prefetch(h_pinned, nbytes, stage, out, ws, copy, compute)
+        compute.synchronize()
+        assert np.array_equal(raw_bytes(out), oracle.relu(raw_bytes(pre), w))
