@@ -184,9 +184,14 @@ __device__ inline unsigned group_or(unsigned m) {
     return m;
 }
 
-// Streaming 16-byte accesses.  Tensor data and the compressed stream are
-// touched once per call; the non-temporal hint keeps them from displacing each
-// other in the caches (a plain copy kernel gains about 10 % from it here).
+// Streaming 16-byte accesses, for what a call touches exactly once: the
+// uncompressed tensor (read by the encoder, written by the decoder) and the
+// encoder's output.  The non-temporal hint keeps such data from displacing other
+// data in the caches (a plain copy kernel gains about 10 % from it here).  The
+// decoder's reads of the compressed stream are ordinary loads: the masks are
+// read twice (pre-pass, then expand), and the value runs of neighbouring waves
+// share cache lines; with the hint those re-reads went back to memory, which
+// cost 10-25 % of the decoder's time at low density.
 typedef unsigned int vec4u __attribute__((ext_vector_type(4)));
 __device__ inline uint4 load16_stream(const void* p) {
     const vec4u v = __builtin_nontemporal_load(reinterpret_cast<const vec4u*>(p));
@@ -312,7 +317,7 @@ __device__ inline void wave_copy_in(unsigned char* stage, const unsigned char* g
     const unsigned first_full = (shift + 15u) >> 4;
     const unsigned last_full = end_valid >> 4;
     for (unsigned q = first_full + lane; q < last_full; q += kWaveSize)
-        *reinterpret_cast<uint4*>(stage + q * 16u) = load16_stream(gbase + q * 16u);
+        *reinterpret_cast<uint4*>(stage + q * 16u) = *reinterpret_cast<const uint4*>(gbase + q * 16u);
     const unsigned head_end = min(end, first_full * 16u);
     const unsigned tail_begin = max(max(shift, last_full * 16u), head_end);
     const unsigned oh = shift + W * lane;
@@ -333,6 +338,49 @@ __device__ inline void wave_copy_in(unsigned char* stage, const unsigned char* g
             *reinterpret_cast<unsigned short*>(stage + o) =
                 o < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + o)
                               : static_cast<unsigned short>(0);
+    }
+}
+
+// The same copy in two halves, so that a wave can have the loads of several
+// steps in flight before it touches LDS.  wave_fetch requests the aligned
+// 16-byte chunks that hold global bytes [shift, end_valid) at gbase (gbase is
+// 16-byte aligned, shift < 16): chunk q goes to lane q % 64, slot q / 64.  A
+// chunk is loaded whole even where the run begins or ends inside it -- an
+// aligned 16-byte chunk never straddles a page, so the access is as safe as
+// that of the bytes wanted -- and what lies at or past end_valid is cleared.
+// wave_commit stores the chunks to LDS at the same offsets.
+constexpr int kFetchSlots = (kStageLoads * kWaveSize * 16 + 16 + 15) / 16 / kWaveSize + 1;   // 5
+
+__device__ inline void wave_fetch(uint4 (&r)[kFetchSlots], const unsigned char* gbase, unsigned end_valid,
+                                  bool streaming, int lane) {
+#pragma unroll
+    for (int k = 0; k < kFetchSlots; ++k) {
+        const unsigned q = static_cast<unsigned>(lane + k * kWaveSize);
+        r[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (q * 16u < end_valid)
+            r[k] = streaming ? load16_stream(gbase + q * 16u)
+                             : *reinterpret_cast<const uint4*>(gbase + q * 16u);
+    }
+}
+
+__device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetchSlots], unsigned end,
+                                   unsigned end_valid, int lane) {
+#pragma unroll
+    for (int k = 0; k < kFetchSlots; ++k) {
+        const unsigned q = static_cast<unsigned>(lane + k * kWaveSize);
+        if (q * 16u >= end) continue;
+        uint4 v = r[k];
+        if (q * 16u + 16u > end_valid) {          // only when the stream is cut short
+            const unsigned valid = end_valid > q * 16u ? end_valid - q * 16u : 0u;   // bytes to keep: 0 .. 15
+            unsigned d[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned lo = 4u * i;
+                d[i] = valid >= lo + 4u ? d[i] : valid > lo ? d[i] & ((1u << (8u * (valid - lo))) - 1u) : 0u;
+            }
+            v = make_uint4(d[0], d[1], d[2], d[3]);
+        }
+        *reinterpret_cast<uint4*>(stage + q * 16u) = v;
     }
 }
 
@@ -782,7 +830,7 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     if (whole) {
 #pragma unroll
         for (int k = 0; k < kChunkLoads; ++k) {
-            const uint4 v = load16_stream(masks + g_chunk + 1024 * k + 4 * tid);
+            const uint4 v = *reinterpret_cast<const uint4*>(masks + g_chunk + 1024 * k + 4 * tid);
             c[k] = __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
         }
     } else {
@@ -903,7 +951,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
     const unsigned* __restrict__ unit_end, const unsigned long long* __restrict__ chunk_prefix,
-    size_t num_groups) {
+    size_t num_groups, bool stream_values) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -943,16 +991,25 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
 
     const bool full_wave = ALIGNED && wave_elem0 + static_cast<size_t>(LOADS) * kWaveSize * E <= n;
     unsigned char* stage = s_stage[wave];
+    // the stored elements of every step are requested before the first is expanded
+    uint4 fetched[kSteps][kFetchSlots];
+    unsigned shift_of[kSteps], end_of[kSteps], end_valid_of[kSteps];
 #pragma unroll
     for (int h = 0; h < kSteps; ++h) {
         const unsigned step_total = step_end[h] - step_begin[h];
         const unsigned long long first = before_chunk + step_begin[h];
         const unsigned char* src = values + first * W;  // wave-uniform
-        const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
+        shift_of[h] = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
         unsigned long long readable = values_avail > first ? values_avail - first : 0ull;
         if (readable > step_total) readable = step_total;
-        wave_copy_in<W>(stage, src - shift, shift, shift + step_total * W,
-                        shift + static_cast<unsigned>(readable) * W, lane);
+        end_of[h] = shift_of[h] + step_total * W;
+        end_valid_of[h] = shift_of[h] + static_cast<unsigned>(readable) * W;
+        wave_fetch(fetched[h], src - shift_of[h], readable != 0 ? end_valid_of[h] : 0u, stream_values, lane);
+    }
+#pragma unroll
+    for (int h = 0; h < kSteps; ++h) {
+        const unsigned shift = shift_of[h];
+        wave_commit(stage, fetched[h], end_of[h], end_valid_of[h] > shift ? end_valid_of[h] : 0u, lane);
         // stored elements of the step before each of its masks (lane i holds mask i)
         const unsigned cnt = __popc(m[h]);
         unsigned incl = cnt;
@@ -1268,7 +1325,8 @@ inline int choose_loads(size_t n, int w, bool aligned) {
 // The decoder's waves are independent, so its tile only sets how many staging
 // steps a wave does one after the other: one step (16 KB tiles) measures best
 // at every size.
-inline int choose_decoder_loads(size_t, int, bool) {
+inline int choose_decoder_loads(size_t, int, bool aligned) {
+    if (!aligned) return kMinLoads;
     return ZVC_FORCE_DECODER_LOADS != 0 ? ZVC_FORCE_DECODER_LOADS : kMinLoads;
 }
 
@@ -1301,8 +1359,12 @@ void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
                           unsigned char* out, const unsigned* unit_end,
                           const unsigned long long* chunk_prefix, size_t groups) {
+    // Dense streams (3/4 of the elements stored, or more) are read with the streaming
+    // hint: little of a cache line is then shared between waves, and the hint is worth
+    // 5 % there; sparser streams are read through the caches (see load16_stream).
+    const bool stream_values = avail >= n / 4 * 3;
     hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, unit_end, chunk_prefix, groups);
+                       masks, values, avail, n, out, unit_end, chunk_prefix, groups, stream_values);
 }
 
 // Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
