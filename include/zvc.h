@@ -33,6 +33,11 @@
  *     compressed buffer must be aligned to 4 bytes.  16-byte alignment of the
  *     uncompressed tensor selects the fast kernels; anything less still works.
  *   - input and output ranges must not overlap.
+ *   - reads are made in aligned 16-byte chunks: a kernel may read the whole
+ *     aligned 16-byte chunk that holds the first or the last byte of a buffer
+ *     it is given (such a chunk never straddles a page, so this touches no
+ *     memory the bytes themselves do not), and ignores what is not the buffer's.
+ *     Nothing is ever written outside the output ranges.
  *   - device work is enqueued on the given stream and the call returns
  *     without waiting for it (zvc_offload is the one exception, see there).
  *   - n = 0 is legal.
@@ -147,8 +152,9 @@ zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, siz
  * (section 5.2, decompression engine: popcount of the mask gives the words a
  * span consumes, a prefix sum gives each slot's source, slots take a stored
  * word or zero).  comp_bytes is the number of readable bytes at d_comp (at
- * least zvc_mask_bytes(n)); the kernel never reads past it: if damaged masks
- * ask for more values than are there, the missing elements decode as zero. */
+ * least zvc_mask_bytes(n)); the kernel reads no stored element past it: if
+ * damaged masks ask for more values than are there, the missing elements decode
+ * as zero. */
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,
                           void* d_ws, size_t ws, hipStream_t stream);
 
