@@ -280,33 +280,63 @@ __device__ inline unsigned element_of(const uint4& v, int c) {
     return (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
 }
 
-// Copies LDS bytes [shift, end) to global memory at gbase + same offsets, where
-// gbase is 16-byte aligned and wave-uniform: whole 16-byte chunks as one store,
-// the ragged head and tail (under 16 bytes each) element by element.
+// Writes out what a wave has staged so far, whole 128-byte lines only where it
+// can.  The wave's packed run goes through its LDS slice like through a queue:
+// slice offset p holds global byte gline + p (gline is 128-byte aligned and
+// wave-uniform), and [lo, end) is staged but not yet written.  Complete lines
+// leave as 16-byte stores; the bytes before the run's first line boundary and,
+// with `last`, those after its last one leave element by element; an unfinished
+// line at the end otherwise stays behind and is moved to the front of the slice,
+// where the next step continues it.  So a wave writes two partial lines per
+// tile instead of two per step: partial-line writes cost the memory system about
+// as much as whole lines.  Returns nothing; updates gline, lo and end.
 template <int W>
-__device__ inline void wave_copy_out(unsigned char* gbase, const unsigned char* stage,
-                                     unsigned shift, unsigned end, int lane) {
-    const unsigned first_full = (shift + 15u) >> 4;   // chunk indices
-    const unsigned last_full = end >> 4;
-    for (unsigned q = first_full + lane; q < last_full; q += kWaveSize)
-        store16_stream(gbase + q * 16u, *reinterpret_cast<const uint4*>(stage + q * 16u));
-    const unsigned head_end = min(end, first_full * 16u);
-    const unsigned tail_begin = max(max(shift, last_full * 16u), head_end);
-    const unsigned oh = shift + W * lane;
-    const unsigned ot = tail_begin + W * lane;
-    if (W == 4) {
-        if (oh < head_end)
-            *reinterpret_cast<unsigned*>(gbase + oh) = *reinterpret_cast<const unsigned*>(stage + oh);
-        if (ot < end)
-            *reinterpret_cast<unsigned*>(gbase + ot) = *reinterpret_cast<const unsigned*>(stage + ot);
-    } else {
-        if (oh < head_end)
-            *reinterpret_cast<unsigned short*>(gbase + oh) =
-                *reinterpret_cast<const unsigned short*>(stage + oh);
-        if (ot < end)
-            *reinterpret_cast<unsigned short*>(gbase + ot) =
-                *reinterpret_cast<const unsigned short*>(stage + ot);
+__device__ inline void wave_flush_lines(unsigned char*& gline, unsigned char* stage, unsigned& lo,
+                                        unsigned& end, bool last, int lane) {
+    const unsigned first_line = (lo + 127u) >> 7;
+    const unsigned last_line = end >> 7;
+    if (!last && last_line < first_line + ((lo & 127u) != 0u ? 0u : 1u)) return;   // no line completed yet
+    // the run's head: from lo to its first line boundary
+    const unsigned head_end = min(end, first_line << 7);
+    if (lo + W * lane < head_end) {
+        const unsigned o = lo + W * lane;
+        if (W == 4)
+            *reinterpret_cast<unsigned*>(gline + o) = *reinterpret_cast<const unsigned*>(stage + o);
+        else
+            *reinterpret_cast<unsigned short*>(gline + o) = *reinterpret_cast<const unsigned short*>(stage + o);
     }
+    // whole lines
+    for (unsigned q = (first_line << 3) + lane; q < (last_line << 3); q += kWaveSize)
+        store16_stream(gline + q * 16u, *reinterpret_cast<const uint4*>(stage + q * 16u));
+    const unsigned tail_begin = max(head_end, last_line << 7);
+    if (last) {
+        const unsigned o = tail_begin + W * lane;
+        if (o < end) {
+            if (W == 4)
+                *reinterpret_cast<unsigned*>(gline + o) = *reinterpret_cast<const unsigned*>(stage + o);
+            else
+                *reinterpret_cast<unsigned short*>(gline + o) = *reinterpret_cast<const unsigned short*>(stage + o);
+        }
+        lo = end;
+        return;
+    }
+    // the unfinished line moves to the front of the slice (source and destination do not overlap:
+    // a line was completed, so tail_begin >= 128)
+    const unsigned rem = end - tail_begin;
+    unsigned keep = 0;
+    const bool mine = static_cast<unsigned>(W * lane) < rem;
+    if (mine) {
+        if (W == 4) keep = *reinterpret_cast<const unsigned*>(stage + tail_begin + W * lane);
+        else keep = *reinterpret_cast<const unsigned short*>(stage + tail_begin + W * lane);
+    }
+    wave_lds_sync();
+    if (mine) {
+        if (W == 4) *reinterpret_cast<unsigned*>(stage + W * lane) = keep;
+        else *reinterpret_cast<unsigned short*>(stage + W * lane) = static_cast<unsigned short>(keep);
+    }
+    gline += tail_begin;
+    lo = 0;
+    end = rem;
 }
 
 // The mirror: global bytes [shift, end) at gbase into LDS at the same offsets;
@@ -612,7 +642,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     static_assert(!WINDOWED || G::kEncStageLoads == kStageLoads, "the windowed decoder expands four windows per wave");
 
     __shared__ __align__(16) unsigned char
-        s_stage[kWaves][G::kEncWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0)];
+        s_stage[kWaves][G::kEncWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0) + 128];
     __shared__ unsigned s_wave_total[kWaves];
     __shared__ unsigned long long s_prefix;
 
@@ -708,10 +738,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
 
     // ---- compaction (section 5.2: shift non-zeros to their packed slots).
     //      Each wave stages kEncStageLoads loads at a time in its own LDS slice in
-    //      packed order, then copies the run out.  LDS byte p of the slice
-    //      corresponds to global byte (dst - shift) + p, so 16-byte chunks are
-    //      aligned on both sides.
+    //      packed order and writes out the lines that are complete (see
+    //      wave_flush_lines): slice byte p corresponds to global byte gline + p.
     unsigned char* stage = s_stage[wave];
+    unsigned char* gline = nullptr;
+    unsigned pend_lo = 0, pend_end = 0;
 #pragma unroll
     for (int h = 0; h < G::kEncStageSteps; ++h) {
         const unsigned first_rank = run[h * G::kEncStageLoads];
@@ -726,7 +757,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         const unsigned step_bytes = step_total * W + 4u * valid_groups;
         unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W +   // wave-uniform
                              (WINDOWED ? 4 * (window_group0 < a.num_groups ? window_group0 : a.num_groups) : 0);
-        const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 15u);
+        if (h == 0) {   // later steps continue where the previous one ended: dst == gline + pend_end
+            pend_lo = pend_end = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 127u);
+            gline = dst - pend_lo;
+        }
+        const unsigned shift = pend_end;
         if (WINDOWED && lane == 0) {
             // the byte offset of every window that exists: its masks before it, its kept elements before it
 #pragma unroll
@@ -773,7 +808,8 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
             __builtin_amdgcn_sched_barrier(0);
         }
         wave_lds_sync();
-        wave_copy_out<W>(dst - shift, stage, shift, shift + step_bytes, lane);
+        pend_end = shift + step_bytes;
+        wave_flush_lines<W>(gline, stage, pend_lo, pend_end, h == G::kEncStageSteps - 1, lane);
         wave_lds_sync();
     }
     ZVC_TRACE_POINT(tile, 5);
