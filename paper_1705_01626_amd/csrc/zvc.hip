@@ -50,9 +50,6 @@ constexpr int kStageLoads = 4;                // 16-byte loads a wave stages thr
 constexpr int kBlockTiles = 64;               // one running prefix is published per 64 tiles
 constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
 
-#ifndef ZVC_ENC_STAGE_LOADS
-#define ZVC_ENC_STAGE_LOADS 4
-#endif
 // A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
 template <int W, int LOADS>
 struct Geometry {
@@ -69,10 +66,6 @@ struct Geometry {
     // (16 bytes so the slice can mirror the destination's alignment)
     static constexpr int kWaveStageBytes = kStageLoads * kWaveSize * 16 + 16;
     static_assert(LOADS % kStageLoads == 0, "tile is staged in whole steps");
-    // loads the encoder stages at a time (a build-time knob; 4 and 8 measure alike, 16 costs occupancy)
-    static constexpr int kEncStageLoads = LOADS >= ZVC_ENC_STAGE_LOADS ? ZVC_ENC_STAGE_LOADS : kStageLoads;
-    static constexpr int kEncStageSteps = LOADS / kEncStageLoads;
-    static constexpr int kEncWaveStageBytes = kEncStageLoads * kWaveSize * 16 + 16;
 };
 
 // Workspace header.  Lives at the start of the caller's workspace.
@@ -637,12 +630,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
-    constexpr int kStepGroups = G::kEncStageLoads * G::kGroupsPerLoad;   // masks of one window: 32 | 64
+    constexpr int kStepGroups = kStageLoads * G::kGroupsPerLoad;   // masks of one window: 32 | 64
     constexpr int kMaskUnits = 4 / W;                                    // a mask in units of W bytes
-    static_assert(!WINDOWED || G::kEncStageLoads == kStageLoads, "the windowed decoder expands four windows per wave");
 
     __shared__ __align__(16) unsigned char
-        s_stage[kWaves][G::kEncWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0) + 128];
+        s_stage[kWaves][G::kWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0) + 128];
     __shared__ unsigned s_wave_total[kWaves];
     __shared__ unsigned long long s_prefix;
 
@@ -737,18 +729,18 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     if (wave == 0 && lane == 0) finish_arrive(a.hdr, tile);
 
     // ---- compaction (section 5.2: shift non-zeros to their packed slots).
-    //      Each wave stages kEncStageLoads loads at a time in its own LDS slice in
+    //      Each wave stages kStageLoads loads at a time in its own LDS slice in
     //      packed order and writes out the lines that are complete (see
     //      wave_flush_lines): slice byte p corresponds to global byte gline + p.
     unsigned char* stage = s_stage[wave];
     unsigned char* gline = nullptr;
     unsigned pend_lo = 0, pend_end = 0;
 #pragma unroll
-    for (int h = 0; h < G::kEncStageSteps; ++h) {
-        const unsigned first_rank = run[h * G::kEncStageLoads];
-        const unsigned step_total = run[(h + 1) * G::kEncStageLoads] - first_rank;
+    for (int h = 0; h < G::kStageSteps; ++h) {
+        const unsigned first_rank = run[h * kStageLoads];
+        const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
         // windowed: the step is four windows (one per load), whose groups may end with the tensor
-        const size_t step = (static_cast<size_t>(tile) * kWaves + wave) * G::kEncStageSteps + h;
+        const size_t step = (static_cast<size_t>(tile) * kWaves + wave) * G::kStageSteps + h;
         const size_t window_group0 = step * kStepGroups;
         const unsigned valid_groups =
             !WINDOWED || window_group0 >= a.num_groups ? 0u
@@ -765,15 +757,15 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         if (WINDOWED && lane == 0) {
             // the byte offset of every window that exists: its masks before it, its kept elements before it
 #pragma unroll
-            for (int jj = 0; jj < G::kEncStageLoads; ++jj)
+            for (int jj = 0; jj < kStageLoads; ++jj)
                 if (static_cast<unsigned>(jj * G::kGroupsPerLoad) < valid_groups)
-                    a.offsets[step * G::kEncStageLoads + jj] =
+                    a.offsets[step * kStageLoads + jj] =
                         static_cast<unsigned long long>(dst - a.values) + 4u * jj * G::kGroupsPerLoad +
-                        W * (run[h * G::kEncStageLoads + jj] - first_rank);
+                        W * (run[h * kStageLoads + jj] - first_rank);
         }
 #pragma unroll
-        for (int jj = 0; jj < G::kEncStageLoads; ++jj) {
-            const int j = h * G::kEncStageLoads + jj;
+        for (int jj = 0; jj < kStageLoads; ++jj) {
+            const int j = h * kStageLoads + jj;
             // rank of the lane's first element within the step
             const unsigned rank0 = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
             const unsigned group = static_cast<unsigned>(jj * G::kGroupsPerLoad + lane / LPG);
@@ -809,7 +801,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         }
         wave_lds_sync();
         pend_end = shift + step_bytes;
-        wave_flush_lines<W>(gline, stage, pend_lo, pend_end, h == G::kEncStageSteps - 1, lane);
+        wave_flush_lines<W>(gline, stage, pend_lo, pend_end, h == G::kStageSteps - 1, lane);
         wave_lds_sync();
     }
     ZVC_TRACE_POINT(tile, 5);
