@@ -332,40 +332,9 @@ __device__ inline void wave_flush_lines(unsigned char*& gline, unsigned char* st
     end = rem;
 }
 
-// The mirror: global bytes [shift, end) at gbase into LDS at the same offsets;
-// bytes at or past end_valid (<= end) are not read and become zero.
-template <int W>
-__device__ inline void wave_copy_in(unsigned char* stage, const unsigned char* gbase,
-                                    unsigned shift, unsigned end, unsigned end_valid, int lane) {
-    const unsigned first_full = (shift + 15u) >> 4;
-    const unsigned last_full = end_valid >> 4;
-    for (unsigned q = first_full + lane; q < last_full; q += kWaveSize)
-        *reinterpret_cast<uint4*>(stage + q * 16u) = *reinterpret_cast<const uint4*>(gbase + q * 16u);
-    const unsigned head_end = min(end, first_full * 16u);
-    const unsigned tail_begin = max(max(shift, last_full * 16u), head_end);
-    const unsigned oh = shift + W * lane;
-    if (W == 4) {
-        if (oh < head_end)
-            *reinterpret_cast<unsigned*>(stage + oh) =
-                oh < end_valid ? *reinterpret_cast<const unsigned*>(gbase + oh) : 0u;
-        // under 16 bytes unless the stream is cut short (then the rest is zero fill)
-        for (unsigned o = tail_begin + W * lane; o < end; o += W * kWaveSize)
-            *reinterpret_cast<unsigned*>(stage + o) =
-                o < end_valid ? *reinterpret_cast<const unsigned*>(gbase + o) : 0u;
-    } else {
-        if (oh < head_end)
-            *reinterpret_cast<unsigned short*>(stage + oh) =
-                oh < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + oh)
-                               : static_cast<unsigned short>(0);
-        for (unsigned o = tail_begin + W * lane; o < end; o += W * kWaveSize)
-            *reinterpret_cast<unsigned short*>(stage + o) =
-                o < end_valid ? *reinterpret_cast<const unsigned short*>(gbase + o)
-                              : static_cast<unsigned short>(0);
-    }
-}
-
-// The same copy in two halves, so that a wave can have the loads of several
-// steps in flight before it touches LDS.  wave_fetch requests the aligned
+// Global bytes into the LDS slice at the same offsets modulo 16, in two halves,
+// so that a wave can have the loads of several steps in flight before it
+// touches LDS.  wave_fetch requests the aligned
 // 16-byte chunks that hold global bytes [shift, end_valid) at gbase (gbase is
 // 16-byte aligned, shift < 16): chunk q goes to lane q % 64, slot q / 64.  A
 // chunk is loaded whole even where the run begins or ends inside it -- an
@@ -1142,7 +1111,12 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
     const unsigned limit = shift + bytes;
     unsigned char* stage = s_stage[wave];
-    wave_copy_in<W>(stage, src - shift, shift, limit, limit, lane);
+    {
+        static_assert(kMaxBytes + 16 <= kFetchSlots * kWaveSize * 16, "the windows fit the fetch slots");
+        uint4 fetched[kFetchSlots];
+        wave_fetch(fetched, src - shift, bytes != 0 ? limit : 0u, false, lane);
+        wave_commit(stage, fetched, limit, bytes != 0 ? limit : 0u, lane);
+    }
     wave_lds_sync();
 
     // ---- lanes 0..3: the serial walk over one window's masks each
