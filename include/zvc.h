@@ -177,6 +177,13 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
 /* Number of windows for n elements of width w: ceil(n*w / 1024).  0 for a bad w. */
 size_t zvc_window_count(size_t n, int w);
 
+/* Host-side consistency check of a windowed stream and its table, both in HOST
+ * memory: ZVC_OK iff the table starts at 0, ends at `bytes`, and every window,
+ * walked mask by mask (a mask, then as many elements as it has bits set), ends
+ * exactly where the next one begins; the last mask has no bit set past n. */
+zvc_status zvc_window_check_stream(const void* h_stream, uint64_t bytes, const uint64_t* h_offsets,
+                                   size_t n, int w);
+
 /* Compress into the windowed stream.  d_out / out_cap / d_bytes / workspace as
  * for zvc_compress; d_offsets is a device array of zvc_window_count(n, w) + 1
  * 64-bit words (8-byte aligned, not overlapping the other buffers). */

@@ -1522,6 +1522,34 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
     return bytes == 4 * groups + static_cast<uint64_t>(w) * kept ? ZVC_OK : ZVC_E_CORRUPT;
 }
 
+zvc_status zvc_window_check_stream(const void* h_stream, uint64_t bytes, const uint64_t* h_offsets,
+                                   size_t n, int w) {
+    if (w != 2 && w != 4) return ZVC_E_WIDTH;
+    if (h_offsets == nullptr || (h_stream == nullptr && bytes != 0)) return ZVC_E_ARG;
+    const size_t windows = zvc_window_count(n, w);
+    const size_t groups = div_up(n, 32);
+    const size_t groups_per_window = kWindowBytes / static_cast<size_t>(w) / 32;
+    const unsigned char* p = static_cast<const unsigned char*>(h_stream);
+    if (h_offsets[0] != 0 || h_offsets[windows] != bytes) return ZVC_E_CORRUPT;
+    for (size_t k = 0; k < windows; ++k) {
+        uint64_t pos = h_offsets[k];
+        const uint64_t end = h_offsets[k + 1];
+        if (end < pos || end > bytes) return ZVC_E_CORRUPT;
+        const size_t g0 = k * groups_per_window;
+        const size_t g1 = g0 + groups_per_window < groups ? g0 + groups_per_window : groups;
+        for (size_t g = g0; g < g1; ++g) {      // the walk of section 5.2: mask, then its popcount of elements
+            if (pos + 4 > end) return ZVC_E_CORRUPT;
+            const uint32_t m = static_cast<uint32_t>(p[pos]) | (static_cast<uint32_t>(p[pos + 1]) << 8) |
+                               (static_cast<uint32_t>(p[pos + 2]) << 16) |
+                               (static_cast<uint32_t>(p[pos + 3]) << 24);
+            if (g == groups - 1 && n % 32 != 0 && (m >> (n % 32)) != 0) return ZVC_E_CORRUPT;
+            pos += 4 + static_cast<uint64_t>(w) * static_cast<uint64_t>(__builtin_popcount(m));
+        }
+        if (pos != end) return ZVC_E_CORRUPT;
+    }
+    return ZVC_OK;
+}
+
 zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream) {
     if (d_ws == nullptr) return ZVC_E_ARG;
     if (!aligned_to(d_ws, 256)) return ZVC_E_ALIGN;

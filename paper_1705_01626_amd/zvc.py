@@ -26,7 +26,7 @@ EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
            "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
-           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_compress", "zvc_window_decompress")
+           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream", "zvc_window_compress", "zvc_window_decompress")
 
 _lib = None
 
@@ -66,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
     lib.zvc_window_count.restype = sz
     lib.zvc_window_count.argtypes = [sz, ci]
+    lib.zvc_window_check_stream.restype = ci
+    lib.zvc_window_check_stream.argtypes = [vp, u64, vp, sz, ci]
     lib.zvc_window_compress.restype = ci
     lib.zvc_window_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, vp, sz, vp]
     lib.zvc_window_decompress.restype = ci
@@ -124,6 +126,15 @@ def zvc_check_stream(h_comp: torch.Tensor, nbytes: int, n: int, w: int) -> int:
     Returns the status code (ZVC_OK or an error), it does not raise."""
     assert h_comp.device.type == "cpu" and h_comp.is_contiguous()
     return int(load().zvc_check_stream(h_comp.data_ptr(), nbytes, n, w))
+
+
+def zvc_window_check_stream(h_stream: torch.Tensor, nbytes: int, h_offsets: torch.Tensor, n: int,
+                            w: int) -> int:
+    """Host-side consistency check of a windowed stream (CPU uint8 tensor) and its table (CPU
+    int64 tensor).  Returns the status code, it does not raise."""
+    assert h_stream.device.type == "cpu" and h_offsets.device.type == "cpu"
+    assert h_stream.is_contiguous() and h_offsets.is_contiguous() and h_offsets.dtype == torch.int64
+    return int(load().zvc_window_check_stream(h_stream.data_ptr(), nbytes, h_offsets.data_ptr(), n, w))
 
 
 def zvc_set_lookback_patience(polls: int) -> None:

@@ -127,6 +127,33 @@ def test_check_stream_on_host(oracle):
     assert zvc.zvc_check_stream(torch.zeros(4, dtype=torch.uint8), 4, 32, 3) == zvc.ZVC_E_WIDTH
 
 
+def test_window_check_stream_on_host(oracle):
+    """zvc_window_check_stream accepts the oracle's windowed streams and tables and rejects
+    damaged ones: a flipped presence bit, a shifted table entry, a wrong total, a bit past n."""
+    rng = np.random.default_rng(3)
+    for w in (2, 4):
+        per = 1024 // w
+        for n in (0, 1, 33, per, per + 1, 5 * per + 77):
+            dtype = np.uint32 if w == 4 else np.uint16
+            x = rng.integers(0, 3, size=n).astype(dtype)
+            s, offs = oracle.window_compress(x, w, per)
+            assert zvc.zvc_window_count(n, w) == offs.size - 1
+            t = torch.from_numpy(np.concatenate([s, np.zeros(16, np.uint8)]))
+            o = torch.from_numpy(offs.astype(np.int64))
+            assert zvc.zvc_window_check_stream(t, s.size, o, n, w) == zvc.ZVC_OK
+            if n:
+                t2 = t.clone()
+                t2[0] ^= 1
+                assert zvc.zvc_window_check_stream(t2, s.size, o, n, w) == zvc.ZVC_E_CORRUPT
+                assert zvc.zvc_window_check_stream(t, s.size + w, o, n, w) == zvc.ZVC_E_CORRUPT
+            if offs.size > 2:
+                o2 = o.clone()
+                o2[1] += w
+                assert zvc.zvc_window_check_stream(t, s.size, o2, n, w) == zvc.ZVC_E_CORRUPT
+    assert zvc.zvc_window_check_stream(torch.zeros(4, dtype=torch.uint8), 4,
+                                       torch.zeros(2, dtype=torch.int64), 32, 3) == zvc.ZVC_E_WIDTH
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(zvc, "_lib", None)
     monkeypatch.setattr(zvc, "LIBRARY", str(tmp_path / "nope.so"))
