@@ -412,44 +412,49 @@ __device__ inline unsigned long long tile_exclusive_prefix(unsigned* counts,
     if (lane == 0) store32(counts + tile, kCountValid | count);
     unsigned long long exclusive = 0;
     if (tile != 0) {
-        const long long t = static_cast<long long>(tile);
+        const int t = static_cast<int>(tile);
+        // nearest published block prefix; before block 0 the prefix is 0
+        int bb = t / kBlockTiles - 1;
+        unsigned long long base = 0;
+        int lo = 0;
+        while (true) {
+            const int idx = bb - lane;
+            const unsigned long long pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;
+            const unsigned long long have = __ballot((pv & kPrefixValid) != 0);
+            if (have) {
+                const int k = __ffsll(static_cast<long long>(have)) - 1;
+                base = __shfl(pv, k) & ~kPrefixValid;
+                lo = (bb - k + 1) * kBlockTiles;   // first tile after that block
+                break;
+            }
+            bb -= kWaveSize;
+        }
+        // Counts of tiles lo .. t-1, a pair per 8-byte load (lo is a multiple of 64:
+        // pairs are aligned).  A lane adds up its pairs in order as far as they are
+        // published; a later round asks again only for what was missing, so the
+        // waiting re-reads no more than the newest lines of counts.
+        int next = lo + 2 * lane;      // the lane's first pair not added yet
+        unsigned sum = 0;              // a lane adds few counts, each below 2^16
         unsigned polls = 0;
         while (true) {
-            // nearest published block prefix; before block 0 the prefix is 0
-            long long bb = t / kBlockTiles - 1;
-            unsigned long long base = 0;
-            long long lo = 0;
-            while (true) {
-                const long long idx = bb - lane;
-                const unsigned long long pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;
-                const unsigned long long have = __ballot((pv & kPrefixValid) != 0);
-                if (have) {
-                    const int k = __ffsll(static_cast<long long>(have)) - 1;
-                    base = __shfl(pv, k) & ~kPrefixValid;
-                    lo = (bb - k + 1) * kBlockTiles;   // first tile after that block
-                    break;
-                }
-                bb -= kWaveSize;
-            }
-            // counts of tiles lo .. t-1 (lo is a multiple of 64: pairs are 8-byte aligned)
-            unsigned long long sum = 0;
-            long long hole = -1;
+            int hole = -1;
 #pragma unroll 1
-            for (long long i = lo + 2 * lane; i < t; i += 2 * kWaveSize) {
+            for (int i = next; i < t; i += 2 * kWaveSize) {
                 const unsigned long long pair =
                     load64(reinterpret_cast<const unsigned long long*>(counts + i));
                 const unsigned c0 = static_cast<unsigned>(pair);
-                const unsigned c1 = static_cast<unsigned>(pair >> 32);
-                if (!(c0 & kCountValid) && hole < 0) hole = i;
-                sum += c0 & ~kCountValid;
-                if (i + 1 < t) {
-                    if (!(c1 & kCountValid) && hole < 0) hole = i + 1;
-                    sum += c1 & ~kCountValid;
+                const unsigned c1 = i + 1 < t ? static_cast<unsigned>(pair >> 32) : kCountValid;
+                if (hole >= 0) continue;
+                if (c0 & c1 & kCountValid) {
+                    sum += (c0 & ~kCountValid) + (c1 & ~kCountValid);
+                    next = i + 2 * kWaveSize;
+                } else {
+                    hole = (c0 & kCountValid) ? i + 1 : i;
                 }
             }
             const unsigned long long holes = __ballot(hole >= 0);
             if (!holes) {
-                exclusive = base + wave_sum(sum);
+                exclusive = base + wave_sum(static_cast<unsigned long long>(sum));
                 break;
             }
             if (polls < patience) {
@@ -459,7 +464,7 @@ __device__ inline unsigned long long tile_exclusive_prefix(unsigned* counts,
             }
             // help one unpublished predecessor, then look again without waiting anew
             const int hole_lane = __ffsll(static_cast<long long>(holes)) - 1;
-            const long long q = __shfl(hole, hole_lane);
+            const int q = __shfl(hole, hole_lane);
             const unsigned helped_count = count_tile(static_cast<unsigned>(q), lane);
             unsigned old = 0;
             if (lane == 0) {
