@@ -148,6 +148,24 @@ zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t o
 zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                              uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream);
 
+/* Compression into a buffer below the worst case, for streams that stay in GPU
+ * memory (section 9, compression for GPU footprint reduction: the saving is
+ * real only if the buffer is the size of the stream, which is not known before
+ * the call).  relu = 0 compresses d_in as zvc_compress does, relu = 1 as
+ * zvc_relu_compress does.  out_cap may be anything from zvc_mask_bytes(n) up
+ * (less: ZVC_E_CAPACITY).  *d_bytes always receives the size the whole stream
+ * needs.  If that is at most out_cap, d_out holds exactly the stream the
+ * unbounded call writes.  If it is more, the call still returns ZVC_OK (the
+ * size is not known on the host): the mask area is complete, the rest of d_out
+ * up to out_cap is unspecified, and nothing at or past d_out + out_cap has been
+ * written; the caller compares *d_bytes with out_cap and calls again with a
+ * buffer of that size.  (zvc_compressed_size gives the exact size beforehand at
+ * the price of one more read of the tensor.)  Other arguments, errors and
+ * stream ordering as for zvc_compress. */
+zvc_status zvc_compress_bounded(const void* d_in, size_t n, int w, int relu, void* d_out,
+                                size_t out_cap, uint64_t* d_bytes, void* d_ws, size_t ws,
+                                hipStream_t stream);
+
 /* Decompress a stream produced by zvc_compress back into n elements at d_out
  * (section 5.2, decompression engine: popcount of the mask gives the words a
  * span consumes, a prefix sum gives each slot's source, slots take a stored

@@ -559,6 +559,7 @@ struct EncoderArgs {
     size_t num_groups;
     unsigned patience;
     size_t state_bytes;
+    unsigned long long cap_values;   // bytes that may be written at `values`
     unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
 };
 
@@ -706,77 +707,84 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     //      Each wave stages kStageLoads loads at a time in its own LDS slice in
     //      packed order and writes out the lines that are complete (see
     //      wave_flush_lines): slice byte p corresponds to global byte gline + p.
-    unsigned char* stage = s_stage[wave];
-    unsigned char* gline = nullptr;
-    unsigned pend_lo = 0, pend_end = 0;
-#pragma unroll
-    for (int h = 0; h < G::kStageSteps; ++h) {
-        const unsigned first_rank = run[h * kStageLoads];
-        const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
-        // windowed: the step is four windows (one per load), whose groups may end with the tensor
-        const size_t step = (static_cast<size_t>(tile) * kWaves + wave) * G::kStageSteps + h;
-        const size_t window_group0 = step * kStepGroups;
-        const unsigned valid_groups =
-            !WINDOWED || window_group0 >= a.num_groups ? 0u
-            : a.num_groups - window_group0 < kStepGroups ? static_cast<unsigned>(a.num_groups - window_group0)
-                                                         : static_cast<unsigned>(kStepGroups);
-        const unsigned step_bytes = step_total * W + 4u * valid_groups;
-        unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W +   // wave-uniform
-                             (WINDOWED ? 4 * (window_group0 < a.num_groups ? window_group0 : a.num_groups) : 0);
-        if (h == 0) {   // later steps continue where the previous one ended: dst == gline + pend_end
-            pend_lo = pend_end = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 127u);
-            gline = dst - pend_lo;
-        }
-        const unsigned shift = pend_end;
-        if (WINDOWED && lane == 0) {
-            // the byte offset of every window that exists: its masks before it, its kept elements before it
-#pragma unroll
-            for (int jj = 0; jj < kStageLoads; ++jj)
-                if (static_cast<unsigned>(jj * G::kGroupsPerLoad) < valid_groups)
-                    a.offsets[step * kStageLoads + jj] =
-                        static_cast<unsigned long long>(dst - a.values) + 4u * jj * G::kGroupsPerLoad +
-                        W * (run[h * kStageLoads + jj] - first_rank);
-        }
-#pragma unroll
-        for (int jj = 0; jj < kStageLoads; ++jj) {
-            const int j = h * kStageLoads + jj;
-            // rank of the lane's first element within the step
-            const unsigned rank0 = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
-            const unsigned group = static_cast<unsigned>(jj * G::kGroupsPerLoad + lane / LPG);
-            unsigned char* at = stage + shift + W * (rank0 + (WINDOWED ? kMaskUnits * (group + 1u) : 0u));
-            unsigned bits = 0;
-#pragma unroll
-            for (int c = 0; c < E; ++c) {
-                const bool nz = element_kept<W, RELU>(cur[j], c);
-                const unsigned v = element_of<W>(cur[j], c);
-                bits |= (nz ? 1u : 0u) << c;
-                if (__builtin_expect(nz, 1)) {   // predicated: write and advance in the kept lanes only
-                    if (W == 4)
-                        *reinterpret_cast<unsigned*>(at) = v;
-                    else
-                        *reinterpret_cast<unsigned short*>(at) = static_cast<unsigned short>(v);
-                    at += W;
-                }
+    //      A call with a buffer below the worst case (cap_values) writes a tile's
+    //      run only if the run ends inside the buffer; the size is reported anyway.
+    const unsigned long long tile_end_bytes =
+        (exclusive + tile_total) * W +
+        (WINDOWED ? 4ull * min(static_cast<size_t>(tile + 1) * G::kTileGroups, a.num_groups) : 0ull);
+    if (tile_end_bytes <= a.cap_values) {
+        unsigned char* stage = s_stage[wave];
+        unsigned char* gline = nullptr;
+        unsigned pend_lo = 0, pend_end = 0;
+    #pragma unroll
+        for (int h = 0; h < G::kStageSteps; ++h) {
+            const unsigned first_rank = run[h * kStageLoads];
+            const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
+            // windowed: the step is four windows (one per load), whose groups may end with the tensor
+            const size_t step = (static_cast<size_t>(tile) * kWaves + wave) * G::kStageSteps + h;
+            const size_t window_group0 = step * kStepGroups;
+            const unsigned valid_groups =
+                !WINDOWED || window_group0 >= a.num_groups ? 0u
+                : a.num_groups - window_group0 < kStepGroups ? static_cast<unsigned>(a.num_groups - window_group0)
+                                                             : static_cast<unsigned>(kStepGroups);
+            const unsigned step_bytes = step_total * W + 4u * valid_groups;
+            unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W +   // wave-uniform
+                                 (WINDOWED ? 4 * (window_group0 < a.num_groups ? window_group0 : a.num_groups) : 0);
+            if (h == 0) {   // later steps continue where the previous one ended: dst == gline + pend_end
+                pend_lo = pend_end = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 127u);
+                gline = dst - pend_lo;
             }
-            if (WINDOWED) {
-                // the group's first lane puts the mask before the group's elements
-                const unsigned m = group_or<LPG>(bits << field_shift);
-                if (lane_in_group == 0 && group < valid_groups) {
-                    unsigned char* mask_at = stage + shift + W * (rank0 + kMaskUnits * group);
-                    if (W == 4) {
-                        *reinterpret_cast<unsigned*>(mask_at) = m;
-                    } else {
-                        *reinterpret_cast<unsigned short*>(mask_at) = static_cast<unsigned short>(m);
-                        *reinterpret_cast<unsigned short*>(mask_at + 2) = static_cast<unsigned short>(m >> 16);
+            const unsigned shift = pend_end;
+            if (WINDOWED && lane == 0) {
+                // the byte offset of every window that exists: its masks before it, its kept elements before it
+    #pragma unroll
+                for (int jj = 0; jj < kStageLoads; ++jj)
+                    if (static_cast<unsigned>(jj * G::kGroupsPerLoad) < valid_groups)
+                        a.offsets[step * kStageLoads + jj] =
+                            static_cast<unsigned long long>(dst - a.values) + 4u * jj * G::kGroupsPerLoad +
+                            W * (run[h * kStageLoads + jj] - first_rank);
+            }
+    #pragma unroll
+            for (int jj = 0; jj < kStageLoads; ++jj) {
+                const int j = h * kStageLoads + jj;
+                // rank of the lane's first element within the step
+                const unsigned rank0 = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
+                const unsigned group = static_cast<unsigned>(jj * G::kGroupsPerLoad + lane / LPG);
+                unsigned char* at = stage + shift + W * (rank0 + (WINDOWED ? kMaskUnits * (group + 1u) : 0u));
+                unsigned bits = 0;
+    #pragma unroll
+                for (int c = 0; c < E; ++c) {
+                    const bool nz = element_kept<W, RELU>(cur[j], c);
+                    const unsigned v = element_of<W>(cur[j], c);
+                    bits |= (nz ? 1u : 0u) << c;
+                    if (__builtin_expect(nz, 1)) {   // predicated: write and advance in the kept lanes only
+                        if (W == 4)
+                            *reinterpret_cast<unsigned*>(at) = v;
+                        else
+                            *reinterpret_cast<unsigned short*>(at) = static_cast<unsigned short>(v);
+                        at += W;
                     }
                 }
+                if (WINDOWED) {
+                    // the group's first lane puts the mask before the group's elements
+                    const unsigned m = group_or<LPG>(bits << field_shift);
+                    if (lane_in_group == 0 && group < valid_groups) {
+                        unsigned char* mask_at = stage + shift + W * (rank0 + kMaskUnits * group);
+                        if (W == 4) {
+                            *reinterpret_cast<unsigned*>(mask_at) = m;
+                        } else {
+                            *reinterpret_cast<unsigned short*>(mask_at) = static_cast<unsigned short>(m);
+                            *reinterpret_cast<unsigned short*>(mask_at + 2) = static_cast<unsigned short>(m >> 16);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
+            wave_lds_sync();
+            pend_end = shift + step_bytes;
+            wave_flush_lines<W>(gline, stage, pend_lo, pend_end, h == G::kStageSteps - 1, lane);
+            wave_lds_sync();
         }
-        wave_lds_sync();
-        pend_end = shift + step_bytes;
-        wave_flush_lines<W>(gline, stage, pend_lo, pend_end, h == G::kStageSteps - 1, lane);
-        wave_lds_sync();
     }
     ZVC_TRACE_POINT(tile, 5);
 
@@ -1343,10 +1351,10 @@ template <int W, int LOADS, bool ALIGNED>
 void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
                         unsigned* masks, unsigned char* values, ScanState st,
                         unsigned long long* d_bytes, unsigned tiles, size_t groups,
-                        unsigned long long* offsets) {
+                        unsigned long long cap_values, unsigned long long* offsets) {
     const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
                            groups, g_patience.load(std::memory_order_relaxed),
-                           scan_state_bytes(tiles), offsets};
+                           scan_state_bytes(tiles), cap_values, offsets};
     const dim3 grid(tiles), block(kThreads);
     switch (mode) {
         case Encoder::kPlain:
@@ -1410,16 +1418,19 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
     }
 }
 
-zvc_status compress_impl(Encoder mode, const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
-                         uint64_t* d_bytes, uint64_t* d_offsets, void* d_ws, size_t ws,
+// `bounded`: out_cap may be anything from the size of the mask area up; the
+// kernel then writes only runs that end inside it.
+zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n, int w, void* d_out,
+                         size_t out_cap, uint64_t* d_bytes, uint64_t* d_offsets, void* d_ws, size_t ws,
                          hipStream_t stream) {
     if (w != 2 && w != 4) return ZVC_E_WIDTH;
     if (d_bytes == nullptr || ((d_in == nullptr || d_out == nullptr) && n != 0)) return ZVC_E_ARG;
     if (!aligned_to(d_in, static_cast<size_t>(w)) || !aligned_to(d_out, 4) ||
         !aligned_to(d_bytes, 8))
         return ZVC_E_ALIGN;
-    if (out_cap < zvc_max_compressed_bytes(n, w)) return ZVC_E_CAPACITY;
-    if (ranges_overlap(d_in, n * static_cast<size_t>(w), d_out, zvc_max_compressed_bytes(n, w)))
+    const size_t worst = zvc_max_compressed_bytes(n, w);
+    if (out_cap < (bounded ? zvc_mask_bytes(n) : worst)) return ZVC_E_CAPACITY;
+    if (ranges_overlap(d_in, n * static_cast<size_t>(w), d_out, out_cap < worst ? out_cap : worst))
         return ZVC_E_ARG;
     if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
     unsigned long long* out_bytes = reinterpret_cast<unsigned long long*>(d_bytes);
@@ -1442,6 +1453,7 @@ zvc_status compress_impl(Encoder mode, const void* d_in, size_t n, int w, void* 
     launch_compress(w, loads, al, mode, stream, in, n, masks,
                     mode == Encoder::kWindowed ? static_cast<unsigned char*>(d_out) : values,
                     scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups,
+                    !bounded ? ~0ull : out_cap - (mode == Encoder::kWindowed ? 0 : 4 * groups),
                     reinterpret_cast<unsigned long long*>(d_offsets));
     return hip_ok(hipGetLastError());
 }
@@ -1456,8 +1468,8 @@ zvc_status offload_impl(Encoder mode, const void* d_in, size_t n, int w, void* d
     WsHeader* hdr = static_cast<WsHeader*>(d_ws);
     uint64_t* d_size = reinterpret_cast<uint64_t*>(&hdr->size_word);
     // the size word sits in the header and survives until the next offload on this workspace
-    if (zvc_status st = compress_impl(mode, d_in, n, w, d_stage, stage_cap, d_size, nullptr, d_ws, ws,
-                                      compute))
+    if (zvc_status st = compress_impl(mode, false, d_in, n, w, d_stage, stage_cap, d_size, nullptr, d_ws,
+                                      ws, compute))
         return st;
     if (hipMemcpyAsync(h_bytes, d_size, 8, hipMemcpyDeviceToHost, compute) != hipSuccess)
         return ZVC_E_HIP;
@@ -1611,12 +1623,21 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
 
 zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
-    return compress_impl(Encoder::kPlain, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws, stream);
+    return compress_impl(Encoder::kPlain, false, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws,
+                         stream);
 }
 
 zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                              uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
-    return compress_impl(Encoder::kRelu, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws, stream);
+    return compress_impl(Encoder::kRelu, false, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws,
+                         stream);
+}
+
+zvc_status zvc_compress_bounded(const void* d_in, size_t n, int w, int relu, void* d_out, size_t out_cap,
+                                uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
+    if (relu != 0 && relu != 1) return ZVC_E_ARG;
+    return compress_impl(relu ? Encoder::kRelu : Encoder::kPlain, true, d_in, n, w, d_out, out_cap,
+                         d_bytes, nullptr, d_ws, ws, stream);
 }
 
 size_t zvc_window_count(size_t n, int w) {
@@ -1635,7 +1656,7 @@ zvc_status zvc_window_compress(const void* d_in, size_t n, int w, void* d_out, s
             ranges_overlap(d_offsets, table, d_in, n * static_cast<size_t>(w)))
             return ZVC_E_ARG;
     }
-    return compress_impl(Encoder::kWindowed, d_in, n, w, d_out, out_cap, d_bytes, d_offsets, d_ws, ws,
+    return compress_impl(Encoder::kWindowed, false, d_in, n, w, d_out, out_cap, d_bytes, d_offsets, d_ws, ws,
                          stream);
 }
 

@@ -26,7 +26,8 @@ EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
            "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
-           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream", "zvc_window_compress", "zvc_window_decompress")
+           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream",
+           "zvc_window_compress", "zvc_window_decompress", "zvc_compress_bounded")
 
 _lib = None
 
@@ -74,6 +75,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_window_decompress.argtypes = [vp, sz, vp, sz, ci, sz, sz, vp, vp]
     lib.zvc_relu_compress.restype = ci
     lib.zvc_relu_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
+    lib.zvc_compress_bounded.restype = ci
+    lib.zvc_compress_bounded.argtypes = [vp, sz, ci, ci, vp, sz, vp, vp, sz, vp]
     lib.zvc_decompress.restype = ci
     lib.zvc_decompress.argtypes = [vp, sz, sz, ci, vp, vp, sz, vp]
     lib.zvc_offload.restype = ci
@@ -192,6 +195,18 @@ def zvc_relu_compress(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor,
     _check(load().zvc_relu_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
                                     d_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
                                     _stream_handle(stream)), "zvc_relu_compress")
+
+
+def zvc_compress_bounded(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor, ws: torch.Tensor,
+                         relu: bool = False, stream=None, n: Optional[int] = None,
+                         out_cap: Optional[int] = None) -> None:
+    """Enqueue compression of x (relu: of ReLU(x)) into `out`, which may be smaller than the
+    worst case; d_bytes receives the size needed, to be compared with the capacity."""
+    n = x.numel() if n is None else n
+    _check(load().zvc_compress_bounded(x.data_ptr(), n, x.element_size(), int(bool(relu)),
+                                       out.data_ptr(), out.numel() if out_cap is None else out_cap,
+                                       d_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
+                                       _stream_handle(stream)), "zvc_compress_bounded")
 
 
 def zvc_window_count(n: int, w: int) -> int:

@@ -75,6 +75,14 @@ def test_argument_errors_before_any_gpu_call(lib):
     assert c(IN, n, w, OUT, cap, BY, None, wsb, None) == zvc.ZVC_E_ARG
     assert c(IN, n, w, OUT, cap, BY, WS + 64, wsb, None) == zvc.ZVC_E_ALIGN
     assert c(IN, n, w, OUT, cap, BY, WS, wsb - 1, None) == zvc.ZVC_E_WORKSPACE
+    b = lib.zvc_compress_bounded
+    masks = zvc.zvc_mask_bytes(n)
+    assert b(IN, n, 3, 0, OUT, cap, BY, WS, wsb, None) == zvc.ZVC_E_WIDTH
+    assert b(IN, n, w, 2, OUT, cap, BY, WS, wsb, None) == zvc.ZVC_E_ARG
+    assert b(IN, n, w, 0, OUT, masks - 1, BY, WS, wsb, None) == zvc.ZVC_E_CAPACITY
+    assert b(IN, n, w, 1, OUT + 2, masks, BY, WS, wsb, None) == zvc.ZVC_E_ALIGN
+    assert b(IN, n, w, 0, IN + 4000 - masks + 4, masks, BY, WS, wsb, None) == zvc.ZVC_E_ARG  # overlap
+    assert b(IN, n, w, 0, OUT, masks, BY, WS, wsb - 1, None) == zvc.ZVC_E_WORKSPACE
     d = lib.zvc_decompress
     assert d(OUT, cap, n, 5, IN, WS, wsb, None) == zvc.ZVC_E_WIDTH
     assert d(None, cap, n, w, IN, WS, wsb, None) == zvc.ZVC_E_ARG
