@@ -563,26 +563,63 @@ struct EncoderArgs {
     unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
 };
 
-// Issues the loads of `tile`: LOADS x 16 bytes per lane, 1 KB per wave
+// Issues the loads of a tile, LOADS x 16 bytes per lane, 1 KB per wave
 // instruction.  A tile that lies wholly inside an aligned tensor needs no
-// bounds checks.
-template <int W, int LOADS, bool ALIGNED>
-__device__ __forceinline__ void load_tile(uint4 (&data)[LOADS], const EncoderArgs& a, unsigned tile,
-                                          int wave, int lane) {
-    using G = Geometry<W, LOADS>;
-    constexpr int E = G::kElemsPerLane;
-    const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
-    if (ALIGNED && tile_elem0 + G::kTileElems <= a.n) {
-        const uint4* wave_base = reinterpret_cast<const uint4*>(a.in + tile_elem0 * W) +
-                                 static_cast<size_t>(wave) * LOADS * kWaveSize;
+// bounds checks; its loads are issued in the order in which the zero tests use
+// them.
+template <int LOADS>
+__device__ __forceinline__ void load_whole_tile(uint4 (&data)[LOADS], const unsigned char* tile_base,
+                                                int wave, int lane) {
+    const uint4* wave_base =
+        reinterpret_cast<const uint4*>(tile_base) + static_cast<size_t>(wave) * LOADS * kWaveSize;
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) data[j] = load16_stream(wave_base + j * kWaveSize + lane);
+    for (int j = 0; j < LOADS; ++j) {
+        data[j] = load16_stream(wave_base + j * kWaveSize + lane);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// The tile that holds the end of the tensor.  Aligned tensors: every lane loads
+// a whole 16-byte chunk without a branch -- chunks past the last one that holds
+// an element are redirected to that one (an aligned chunk that holds an element
+// lies within the tensor's pages) -- and what is past the end is cleared in
+// registers afterwards, so the loads go out back to back like a whole tile's.
+template <int W, int LOADS, bool ALIGNED>
+__device__ __forceinline__ void load_ragged_tile(uint4 (&data)[LOADS], const EncoderArgs& a,
+                                                 size_t tile_elem0, int wave, int lane) {
+    constexpr int E = 16 / W;
+    if (ALIGNED) {
+        const size_t last_chunk = (a.n - 1) / E;
+        const size_t chunk0 = tile_elem0 / E + static_cast<size_t>(wave) * LOADS * kWaveSize + lane;
+        const uint4* in16 = reinterpret_cast<const uint4*>(a.in);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const size_t q = chunk0 + static_cast<size_t>(j) * kWaveSize;
+            data[j] = load16_stream(in16 + (q < last_chunk ? q : last_chunk));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        const unsigned last_bytes = static_cast<unsigned>(a.n - last_chunk * E) * W;   // 1 .. 16
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const size_t q = chunk0 + static_cast<size_t>(j) * kWaveSize;
+            if (q < last_chunk) continue;
+            const unsigned valid_bytes = q == last_chunk ? last_bytes : 0u;
+            const unsigned raw[4] = {data[j].x, data[j].y, data[j].z, data[j].w};
+            unsigned d[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const unsigned lo = 4u * k;
+                d[k] = valid_bytes >= lo + 4u ? raw[k]
+                     : valid_bytes > lo      ? raw[k] & ((1u << (8u * (valid_bytes - lo))) - 1u)
+                                             : 0u;
+            }
+            data[j] = make_uint4(d[0], d[1], d[2], d[3]);
+        }
     } else {
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
-            const size_t e0 =
-                tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
-            data[j] = load_chunk<W, ALIGNED>(a.in, e0, a.n);
+            const size_t e0 = tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
+            data[j] = load_chunk<W, false>(a.in, e0, a.n);
         }
     }
 }
@@ -620,7 +657,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     ZVC_TRACE_POINT(tile, 0);
 
     uint4 cur[LOADS];
-    load_tile<W, LOADS, ALIGNED>(cur, a, tile, wave, lane);
 
     // ---- zero test, in-wave ranks (section 5.2: prefix sum over the mask bits), masks
     unsigned below16[LOADS / 2];     // kept elements of lower lanes in the same load, 16 bits each
@@ -631,33 +667,46 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     run[0] = 0;
     const int lane_in_group = lane % LPG;
     const unsigned field_shift = static_cast<unsigned>(E * lane_in_group);
-#pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        unsigned bits = 0, below = 0, load_total = 0;
-#pragma unroll
-        for (int c = 0; c < E; ++c) {
-            const bool nz = element_kept<W, RELU>(cur[j], c);
-            const unsigned long long b = __ballot(nz);
-            below = lanes_below(b, below);
-            load_total += static_cast<unsigned>(__popcll(b));
-            bits |= (nz ? 1u : 0u) << c;
+    const auto zero_tests = [&]() __attribute__((always_inline)) {
+    #pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            unsigned bits = 0, below = 0, load_total = 0;
+    #pragma unroll
+            for (int c = 0; c < E; ++c) {
+                const bool nz = element_kept<W, RELU>(cur[j], c);
+                const unsigned long long b = __ballot(nz);
+                below = lanes_below(b, below);
+                load_total += static_cast<unsigned>(__popcll(b));
+                bits |= (nz ? 1u : 0u) << c;
+            }
+            // Pin the rank and the total here and keep the loads' code apart (below).
+            // Left alone the compiler postpones the mbcnt chains until the compaction,
+            // or hoists the compares of all loads, and keeps every ballot of the tile
+            // alive at once, which costs two lane-spills per ballot.
+            below16[j / 2] |= below << (16 * (j % 2));
+            asm volatile("" : "+v"(below16[j / 2]), "+s"(load_total));
+            run[j + 1] = run[j] + load_total;
+            // the group's mask: OR of the lanes' bit fields, each at its position
+            // (the windowed layout forms it again when it stages the load: keeping
+            // it in registers through the scan costs the 64 KB tile a wave of occupancy)
+            if (!WINDOWED) {
+                const unsigned m = group_or<LPG>(bits << field_shift);
+                if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (j == 0) ZVC_TRACE_POINT(tile, 1);
         }
-        // Pin the rank and the total here and keep the loads' code apart (below).
-        // Left alone the compiler postpones the mbcnt chains until the compaction,
-        // or hoists the compares of all loads, and keeps every ballot of the tile
-        // alive at once, which costs two lane-spills per ballot.
-        below16[j / 2] |= below << (16 * (j % 2));
-        asm volatile("" : "+v"(below16[j / 2]), "+s"(load_total));
-        run[j + 1] = run[j] + load_total;
-        // the group's mask: OR of the lanes' bit fields, each at its position
-        // (the windowed layout forms it again when it stages the load: keeping
-        // it in registers through the scan costs the 64 KB tile a wave of occupancy)
-        if (!WINDOWED) {
-            const unsigned m = group_or<LPG>(bits << field_shift);
-            if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (j == 0) ZVC_TRACE_POINT(tile, 1);
+    };
+    // The whole-tile path has its own copy of the zero tests: after a join with
+    // the ragged path the compiler would wait for all the tile's loads before
+    // the first test; on its own it tests each load as it arrives.
+    const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
+    if (ALIGNED && tile_elem0 + G::kTileElems <= a.n) {
+        load_whole_tile<LOADS>(cur, a.in + tile_elem0 * W, wave, lane);
+        zero_tests();
+    } else {
+        load_ragged_tile<W, LOADS, ALIGNED>(cur, a, tile_elem0, wave, lane);
+        zero_tests();
     }
     ZVC_TRACE_POINT(tile, 2);
     // The compaction tests the elements again.  Hide from the compiler that it
