@@ -637,8 +637,11 @@ __device__ __forceinline__ void load_ragged_tile(uint4 (&data)[LOADS], const Enc
 // all earlier kept elements -- and that masks leave with the values instead of
 // going to a mask area.  The scan is the same: a window's byte offset is
 // 4 x (groups before it) + W x (kept elements before it).
+// (The second launch bound asks for six waves per SIMD at 32 KB tiles: the
+// kernel needs 82 VGPRs there when left alone, two more than six waves allow,
+// and fits in 80 without spilling.)
 template <int W, int LOADS, bool ALIGNED, bool RELU, bool WINDOWED>
-__global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
+__global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(EncoderArgs a) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -1369,15 +1372,17 @@ std::atomic<unsigned> g_patience{kDefaultPatience};
 // Tile size of the encoder.  Each tile costs a fixed few nanoseconds of
 // chip-wide time (workgroup launch plus the scan's state traffic), so large
 // tensors use 64 KB tiles; smaller tensors use smaller tiles so that every CU
-// still gets several.
+// still gets several.  The limits are measured crossover points (the chip holds
+// 1024 tiles of 64 KB, 1536 of 32 KB or 2048 of 16 KB at a time; a tensor that
+// just fills one such round is served best by that size).
 #ifndef ZVC_FORCE_LOADS
 #define ZVC_FORCE_LOADS 0
 #endif
 #ifndef ZVC_FORCE_DECODER_LOADS
 #define ZVC_FORCE_DECODER_LOADS 0
 #endif
-constexpr size_t kLargeTensorBytes = size_t{96} << 20;
-constexpr size_t kMediumTensorBytes = size_t{24} << 20;
+constexpr size_t kLargeTensorBytes = size_t{56} << 20;
+constexpr size_t kMediumTensorBytes = size_t{12} << 20;
 
 inline int choose_loads(size_t n, int w, bool aligned) {
     if (!aligned) return kMinLoads;
