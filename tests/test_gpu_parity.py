@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 SIZES = [0, 1, 2, 31, 32, 33, 63, 64, 65, 255, 256, 257, 4095, 4096, 4097, 8191, 8192, 8193,
          3 * 4096 + 17, 5 * 8192 - 1, 100003, (1 << 20) + 5,
-         (1 << 24) + 8192 + 77]  # the last one is large enough for the 32 KB tile kernels
+         5 * (1 << 20) + 777, (1 << 24) + 8192 + 77]  # the last two reach the 32 KB and 64 KB tile kernels at either width
 DTYPES = {4: torch.int32, 2: torch.int16}
 
 
@@ -65,7 +65,7 @@ def test_unaligned_tensor_pointers(oracle, w, offset_elems):
 
 @pytest.mark.parametrize("w,n", [(4, 26000003), (2, 52000007)])
 def test_largest_tile_kernels(oracle, w, n):
-    """Tensors past 96 MB use the 64 KB tile kernels; ragged size, two densities."""
+    """104 MB tensors (64 KB tile kernels at either width); ragged size, two densities."""
     ws = zvc.new_workspace(n, w, DEV)
     for k, density in enumerate((0.08, 0.6)):
         x = random_tensor(n, w, density, seed=n + k)
@@ -217,7 +217,7 @@ def test_scan_wait_that_helps_itself(oracle):
     try:
         zvc.zvc_set_lookback_patience(0)
         helped = 0
-        for w, n in ((4, 3000001), (2, 5000003), (4, (1 << 24) + 12345)):
+        for w, n in ((4, 3000001), (2, 5000003), (4, 6000001), (4, (1 << 24) + 12345)):   # all three tile sizes
             x = random_tensor(n, w, 0.45, seed=w + n)
             ws = zvc.new_workspace(n, w, DEV)
             res = assert_parity(x, oracle, "zero-patience scan", ws)

@@ -10,7 +10,7 @@ from tests.gpu_util import raw_bytes, say
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
 DTYPES = {4: torch.int32, 2: torch.int16}
-SIZES = [0, 1, 31, 32, 33, 255, 4096, 4097, 8193, 100003, (1 << 20) + 5, (1 << 24) + 8192 + 77]
+SIZES = [0, 1, 31, 32, 33, 255, 4096, 4097, 8193, 100003, (1 << 20) + 5, 5 * (1 << 20) + 777, (1 << 24) + 8192 + 77]
 
 
 def signed_words(n, w, zero_fraction, seed):

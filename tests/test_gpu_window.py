@@ -11,7 +11,7 @@ from tests.test_gpu_parity import random_tensor
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
 SIZES = [0, 1, 31, 32, 33, 1023, 1024, 1025, 2047, 2048, 2049, 4096 * 3 + 17, 100003, (1 << 20) + 5,
-         (1 << 24) + 8192 + 77]
+         5 * (1 << 20) + 777, (1 << 24) + 8192 + 77]
 
 
 def window_compress(x, ws=None):
