@@ -25,9 +25,11 @@
 // LDS with aligned 16-byte loads and rebuilds 16 bytes of output per lane from
 // "bit ? next stored element : zero".
 //
-// Two variants share these kernels: a fused ReLU + ZVC encoder (pre-activations
-// in, stream of ReLU(x) out) and the paper's own stream order ("mask, then its
-// non-zeros") in independently decodable 4 KB windows with an offset table.
+// Three variants share these kernels: a fused ReLU + ZVC encoder
+// (pre-activations in, stream of ReLU(x) out), an encoder that writes into a
+// buffer below the worst case and never past it (section 9: streams kept in GPU
+// memory), and the paper's own stream order ("mask, then its non-zeros") in
+// independently decodable 1 KB windows with an offset table.
 
 #include "zvc.h"
 
