@@ -167,3 +167,41 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(zvc, "LIBRARY", str(tmp_path / "nope.so"))
     with pytest.raises(ImportError):
         zvc.load()
+
+
+C_CLIENT = r"""
+#include "zvc.h"
+#include <stdio.h>
+int main(void) {
+    /* host-only entry points, called from plain C through the header's prototypes */
+    if (zvc_mask_bytes(65) != 12) return 1;
+    if (zvc_max_compressed_bytes(65, 2) != 12 + 130) return 2;
+    if (zvc_workspace_bytes(1000, 4) == 0 || zvc_workspace_bytes(1000, 3) != 0) return 3;
+    if (zvc_window_count(1025, 4) != 5) return 4;
+    unsigned int stream[3] = {0x5u, 7u, 9u};             /* one group of 3 elements: mask 101b, two values */
+    if (zvc_check_stream(stream, 12, 3, 4) != ZVC_OK) return 5;
+    if (zvc_check_stream(stream, 8, 3, 4) != ZVC_E_CORRUPT) return 6;
+    if (zvc_compress(0, 10, 4, 0, 0, 0, 0, 0, 0) != ZVC_E_ARG) return 7;
+    printf("%s\n", zvc_status_string(ZVC_E_WIDTH));
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_links(lib, tmp_path):
+    """include/zvc.h compiles as C11 with gcc and a C program links against the library."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "client.c"
+    src.write_text(C_CLIENT)
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(zvc.LIBRARY)
+    cmd = ["gcc", "-std=c11", "-Wall", "-Werror=implicit-function-declaration", "-D__HIP_PLATFORM_AMD__",
+           "-I/opt/rocm/include", "-I" + os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+           "-L" + libdir, "-l:" + os.path.basename(zvc.LIBRARY), "-Wl,-rpath," + libdir]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0, (run.returncode, run.stdout, run.stderr)
+    assert run.stdout.strip() != ""
