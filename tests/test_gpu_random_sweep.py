@@ -2,6 +2,8 @@
 element widths, pointer offsets, sparsity structure (iid, runs of zeros, dense
 and empty stretches) and entry points (plain, fused ReLU, bounded, windowed),
 one workspace reused throughout.  Bit-exact comparison."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -12,8 +14,9 @@ from tests.gpu_util import raw_bytes, say
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
 DTYPES = {4: torch.int32, 2: torch.int16}
-CASES = 60
-MAX_N = 3 << 20
+CASES = int(os.environ.get("ZVC_SWEEP_CASES", "60"))      # more cases for a longer run
+SEED = int(os.environ.get("ZVC_SWEEP_SEED", "20240607"))
+MAX_N = int(os.environ.get("ZVC_SWEEP_MAX_N", str(5 << 20)))   # default reaches the 16 and 32 KB tile kernels
 
 
 def structured_words(rng, n, w):
@@ -46,7 +49,7 @@ def structured_words(rng, n, w):
 
 
 def test_random_sweep(oracle):
-    rng = np.random.default_rng(20240607)
+    rng = np.random.default_rng(SEED)
     ws = zvc.new_workspace(MAX_N + 64, 4, DEV)
     for case in range(CASES):
         w = int(rng.choice([2, 4]))
