@@ -565,22 +565,6 @@ struct EncoderArgs {
     unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
 };
 
-// Issues the loads of a tile, LOADS x 16 bytes per lane, 1 KB per wave
-// instruction.  A tile that lies wholly inside an aligned tensor needs no
-// bounds checks; its loads are issued in the order in which the zero tests use
-// them.
-template <int LOADS>
-__device__ __forceinline__ void load_whole_tile(uint4 (&data)[LOADS], const unsigned char* tile_base,
-                                                int wave, int lane) {
-    const uint4* wave_base =
-        reinterpret_cast<const uint4*>(tile_base) + static_cast<size_t>(wave) * LOADS * kWaveSize;
-#pragma unroll
-    for (int j = 0; j < LOADS; ++j) {
-        data[j] = load16_stream(wave_base + j * kWaveSize + lane);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-}
-
 // The tile that holds the end of the tensor.  Aligned tensors: every lane loads
 // a whole 16-byte chunk without a branch -- chunks past the last one that holds
 // an element are redirected to that one (an aligned chunk that holds an element
@@ -672,7 +656,7 @@ __global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(
     run[0] = 0;
     const int lane_in_group = lane % LPG;
     const unsigned field_shift = static_cast<unsigned>(E * lane_in_group);
-    const auto zero_tests = [&]() __attribute__((always_inline)) {
+    const auto zero_tests = [&](const auto& after_load) __attribute__((always_inline)) {
     #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
             unsigned bits = 0, below = 0, load_total = 0;
@@ -698,20 +682,38 @@ __global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(
                 const unsigned m = group_or<LPG>(bits << field_shift);
                 if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
             }
+            after_load(j);
             __builtin_amdgcn_sched_barrier(0);
             if (j == 0) ZVC_TRACE_POINT(tile, 1);
         }
     };
-    // The whole-tile path has its own copy of the zero tests: after a join with
-    // the ragged path the compiler would wait for all the tile's loads before
-    // the first test; on its own it tests each load as it arrives.
+    // A tile that lies wholly inside an aligned tensor needs no bounds checks
+    // (LOADS x 16 bytes per lane, 1 KB per wave instruction).  It has its own copy
+    // of the zero tests: after a join with the ragged path the compiler would wait
+    // for all the tile's loads before the first test; on its own it tests each
+    // load as it arrives.  A wave keeps kLoadsAhead loads in flight and asks for
+    // the next one after each test: an L1 cache has only some 8 KB of requests in
+    // flight at a time, and whatever else a CU's waves have queued stands in the way
+    // of the scan's and the stores' traffic (all 16 at once: 1-2 % slower on large
+    // tensors; 4: slower again).
     const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
     if (ALIGNED && tile_elem0 + G::kTileElems <= a.n) {
-        load_whole_tile<LOADS>(cur, a.in + tile_elem0 * W, wave, lane);
-        zero_tests();
+        constexpr int kLoadsAhead = LOADS < 8 ? LOADS : 8;
+        const uint4* wave_base = reinterpret_cast<const uint4*>(a.in + tile_elem0 * W) +
+                                 static_cast<size_t>(wave) * LOADS * kWaveSize;
+#pragma unroll
+        for (int j = 0; j < kLoadsAhead; ++j) {
+            cur[j] = load16_stream(wave_base + j * kWaveSize + lane);
+            __builtin_amdgcn_sched_barrier(0);   // in the order in which the tests use them
+        }
+        zero_tests([&](int j) __attribute__((always_inline)) {
+            if (j + kLoadsAhead < LOADS)
+                cur[(j + kLoadsAhead) % LOADS] =
+                    load16_stream(wave_base + (j + kLoadsAhead) * kWaveSize + lane);
+        });
     } else {
         load_ragged_tile<W, LOADS, ALIGNED>(cur, a, tile_elem0, wave, lane);
-        zero_tests();
+        zero_tests([](int) {});
     }
     ZVC_TRACE_POINT(tile, 2);
     // The compaction tests the elements again.  Hide from the compiler that it
