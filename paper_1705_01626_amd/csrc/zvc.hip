@@ -1161,7 +1161,8 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
-    const size_t local = (static_cast<size_t>(blockIdx.x) * kWaves + wave) * kStageLoads;   // first of the wave's windows
+    // first of the wave's windows
+    const size_t local = (static_cast<size_t>(blockIdx.x) * kWaves + wave) * kStageLoads;
     if (local >= num_windows) return;
     const size_t window0 = first_window + local;
     const unsigned windows_here =
@@ -1223,7 +1224,8 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
 #pragma unroll
     for (int jj = 0; jj < kStageLoads; ++jj) {
         if (static_cast<unsigned>(jj) >= windows_here) break;
-        const unsigned in_step = static_cast<unsigned>((jj * kWaveSize + lane) * E);   // element within the wave's part
+        // element within the wave's part
+        const unsigned in_step = static_cast<unsigned>((jj * kWaveSize + lane) * E);
         const int gl = jj * GPL + lane / LPG;
         const unsigned gm = s_mask[wave][gl];
         const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
@@ -1742,12 +1744,16 @@ zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, cons
     unsigned char* out = static_cast<unsigned char*>(d_out);
     const size_t groups = div_up(n, 32);
     const bool al = aligned_to(d_out, 16);
+    const auto launch = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window,
+                           num_windows, out);
+    };
     if (w == 4) {
-        if (al) hipLaunchKernelGGL((window_decode_kernel<4, true>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
-        else hipLaunchKernelGGL((window_decode_kernel<4, false>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
+        if (al) launch(window_decode_kernel<4, true>);
+        else launch(window_decode_kernel<4, false>);
     } else {
-        if (al) hipLaunchKernelGGL((window_decode_kernel<2, true>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
-        else hipLaunchKernelGGL((window_decode_kernel<2, false>), grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window, num_windows, out);
+        if (al) launch(window_decode_kernel<2, true>);
+        else launch(window_decode_kernel<2, false>);
     }
     return hip_ok(hipGetLastError());
 }
