@@ -1017,7 +1017,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
     const unsigned* __restrict__ unit_end, const unsigned long long* __restrict__ chunk_prefix,
-    size_t num_groups, bool stream_values) {
+    size_t num_groups, bool stream_values, bool interleave) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -1032,8 +1032,15 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
-    const size_t wave_elem0 =
-        (static_cast<size_t>(tile) * kWaves + wave) * (static_cast<size_t>(LOADS) * kWaveSize * E);
+    // Which part of the tensor (LOADS KB) the wave expands.  In a row: workgroup i
+    // takes parts 4i .. 4i+3, so the eight XCDs (workgroup i runs on XCD i mod 8)
+    // write 16 KB apiece side by side.  Interleaved: the waves of workgroup i take
+    // parts that are i mod 8 modulo 8, so the XCDs write neighbouring 4 KB blocks at
+    // the same time.  The memory system takes a stream of writes with few reads
+    // among them up to 15 % faster in the second order (the host chooses).
+    const size_t part = interleave ? (static_cast<size_t>(tile / 8) * kWaves + wave) * 8 + tile % 8
+                                   : static_cast<size_t>(tile) * kWaves + wave;
+    const size_t wave_elem0 = part * (static_cast<size_t>(LOADS) * kWaveSize * E);
     if (wave_elem0 >= n) return;                  // nothing of the tensor in this wave's part
     const size_t wave_group0 = wave_elem0 / 32;
     const size_t chunk = wave_group0 / kChunkMasks;
@@ -1438,8 +1445,13 @@ void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
     // hint: little of a cache line is then shared between waves, and the hint is worth
     // 5 % there; sparser streams are read through the caches (see load16_stream).
     const bool stream_values = avail >= n / 4 * 3;
+    // Order in which the parts of the tensor are dealt out to the workgroups (see the
+    // kernel): interleaved where it measures faster, 2-15 % below a twelfth and 2-5 %
+    // above a third of the elements stored; in between the plain order is 1 % ahead.
+    const bool interleave = (avail < n / 12 || avail > n / 3) && n * W >= (size_t{64} << 20);   // (no gain on small tensors)
     hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, unit_end, chunk_prefix, groups, stream_values);
+                       masks, values, avail, n, out, unit_end, chunk_prefix, groups, stream_values,
+                       interleave);
 }
 
 // Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
@@ -1769,7 +1781,8 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     if (n == 0) return ZVC_OK;
     const bool al = aligned_to(d_out, 16);
     const int loads = choose_decoder_loads(n, w, al);
-    const size_t tiles = tiles_for(n, w, loads);
+    // a multiple of 8 workgroups: the interleaved order deals the parts out in rounds of 8
+    const size_t tiles = div_up(tiles_for(n, w, loads), 8) * 8;
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(groups, kChunkMasks);
