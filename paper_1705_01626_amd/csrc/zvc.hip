@@ -1152,7 +1152,7 @@ template <int W, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     const unsigned char* __restrict__ stream, unsigned long long stream_bytes,
     const unsigned long long* __restrict__ offsets, size_t n, size_t num_groups,
-    size_t first_window, size_t num_windows, unsigned char* __restrict__ out) {
+    size_t first_window, size_t num_windows, unsigned char* __restrict__ out, bool interleave) {
     constexpr int E = 16 / W;
     constexpr int LPG = 32 / E;
     constexpr int GPL = kWaveSize / LPG;                    // masks per window: 8 | 16
@@ -1168,8 +1168,11 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
-    // first of the wave's windows
-    const size_t local = (static_cast<size_t>(blockIdx.x) * kWaves + wave) * kStageLoads;
+    // first of the wave's windows: dealt out in a row or, as in the planar decoder,
+    // interleaved over the XCDs
+    const size_t quad = interleave ? (static_cast<size_t>(blockIdx.x / 8) * kWaves + wave) * 8 + blockIdx.x % 8
+                                   : static_cast<size_t>(blockIdx.x) * kWaves + wave;
+    const size_t local = quad * kStageLoads;
     if (local >= num_windows) return;
     const size_t window0 = first_window + local;
     const unsigned windows_here =
@@ -1748,7 +1751,8 @@ zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, cons
                                  ? (first_window + num_windows) * elems_per_window : n;
     const size_t out_bytes = (last_elem - first_window * elems_per_window) * static_cast<size_t>(w);
     if (ranges_overlap(d_stream, stream_bytes, d_out, out_bytes)) return ZVC_E_ARG;
-    const size_t blocks = div_up(num_windows, static_cast<size_t>(kWaves) * kStageLoads);
+    // (a multiple of 8 workgroups for the interleaved order)
+    const size_t blocks = div_up(div_up(num_windows, static_cast<size_t>(kWaves) * kStageLoads), 8) * 8;
     if (blocks > 0x7FFFFFFFull) return ZVC_E_ARG;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const unsigned char* in = static_cast<const unsigned char*>(d_stream);
@@ -1756,9 +1760,11 @@ zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, cons
     unsigned char* out = static_cast<unsigned char*>(d_out);
     const size_t groups = div_up(n, 32);
     const bool al = aligned_to(d_out, 16);
+    // dense streams of large ranges decode 3-8 % faster in the interleaved order, others slower
+    const bool interleave = stream_bytes / 3 > n * static_cast<size_t>(w) / 4 && out_bytes >= (size_t{64} << 20);
     const auto launch = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window,
-                           num_windows, out);
+                           num_windows, out, interleave);
     };
     if (w == 4) {
         if (al) launch(window_decode_kernel<4, true>);

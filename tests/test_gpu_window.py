@@ -155,3 +155,14 @@ def test_window_decoder_survives_garbage_stream_and_table():
     zvc.zvc_window_decompress(comp, nbytes, offsets, n, 0, K, out)
     torch.cuda.synchronize()
     assert torch.equal(out, x)
+
+
+@pytest.mark.parametrize("w", [4, 2])
+def test_window_dense_large_ranges(oracle, w):
+    """Dense streams of ranges of 64 MB and more take the decoder's interleaved order:
+    whole tensor and a large range that starts in the middle, ragged end."""
+    n = 36 * (1 << 20) + 12345
+    ws = zvc.new_workspace(n, w, DEV)
+    K = zvc.zvc_window_count(n, w)
+    x = random_tensor(n, w, 0.92, seed=1234 + w)
+    assert_window_parity(x, oracle, "dense large w=%d" % w, ws, [(3, K - 3), (K // 16, K - K // 16)])
