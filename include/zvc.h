@@ -172,7 +172,9 @@ zvc_status zvc_compress_bounded(const void* d_in, size_t n, int w, int relu, voi
  * word or zero).  comp_bytes is the number of readable bytes at d_comp (at
  * least zvc_mask_bytes(n)); the kernel reads no stored element past it: if
  * damaged masks ask for more values than are there, the missing elements decode
- * as zero. */
+ * as zero.  A comp_bytes larger than the stream is harmless, but the call picks
+ * its access pattern from it (it tells the stream's density): pass the size
+ * the encoder reported where it is known. */
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,
                           void* d_ws, size_t ws, hipStream_t stream);
 
