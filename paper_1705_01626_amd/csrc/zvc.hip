@@ -38,6 +38,7 @@
 #include <atomic>
 #include <cstdint>
 #include <cstring>
+#include <type_traits>
 
 namespace {
 
@@ -68,6 +69,39 @@ struct Geometry {
     // (16 bytes so the slice can mirror the destination's alignment)
     static constexpr int kWaveStageBytes = kStageLoads * kWaveSize * 16 + 16;
     static_assert(LOADS % kStageLoads == 0, "tile is staged in whole steps");
+};
+
+// The encoder's tile.  A wave reads its part of the tensor one dword per lane
+// (a chunk: 256 bytes, 64 fp32 or 128 16-bit elements, 2 or 4 masks), CH chunks
+// per wave, four waves per tile: 16, 32 or 64 KB for CH = 16, 32, 64.  With one
+// element (or one pair) per lane a ballot of the zero test is two masks as they
+// stand and its mbcnt is the packed position, so a chunk costs a handful of
+// vector instructions.  Streaming 4-byte accesses measure as fast as 16-byte
+// ones on this memory system (each wave instruction still covers whole
+// 128-byte lines).
+constexpr int kChunkBytes = 4 * kWaveSize;
+constexpr int kStepChunks = 16;               // chunks a wave stages between two flushes: 4 KB of input
+template <int W, int CH>
+struct EncoderGeometry {
+    static constexpr int kChunkElems = kChunkBytes / W;          // 64 | 128
+    static constexpr int kChunkGroups = kChunkElems / 32;        // masks per chunk: 2 | 4
+    static constexpr int kWaveElems = CH * kChunkElems;
+    static constexpr int kWaveGroups = CH * kChunkGroups;
+    static constexpr int kTileBytes = kWaves * CH * kChunkBytes;
+    static constexpr int kTileElems = kWaves * kWaveElems;
+    static constexpr int kTileGroups = kWaves * kWaveGroups;
+    static constexpr int kSteps = CH / kStepChunks;
+    static constexpr int kMaskRegs = (kWaveGroups + kWaveSize - 1) / kWaveSize;
+    static constexpr int kStepGroups = kStepChunks * kChunkGroups;
+    // the most a step can add to the wave's queue (windowed stream: its masks too)
+    static constexpr int kStepMaxBytes = kStepChunks * kChunkBytes + 4 * kStepGroups;
+    // A wave's LDS queue: room for half the wave's input (what a wave of a tensor
+    // that is at most half non-zero can stage before its tile knows where its run
+    // begins), never less than a carried-over partial line plus one step.
+    static constexpr int kQueueBytes =
+        (CH * kChunkBytes / 2 > kStepMaxBytes ? CH * kChunkBytes / 2 : kStepMaxBytes) + 256;
+    static_assert(CH % kStepChunks == 0, "a wave's chunks are staged in whole steps");
+    static_assert(kTileElems < (1 << 24), "tile totals fit the arrival word");
 };
 
 // Workspace header.  Lives at the start of the caller's workspace.
@@ -275,61 +309,80 @@ __device__ inline unsigned element_of(const uint4& v, int c) {
     return (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
 }
 
-// Writes out what a wave has staged so far, whole 128-byte lines only where it
-// can.  The wave's packed run goes through its LDS slice like through a queue:
-// slice offset p holds global byte gline + p (gline is 128-byte aligned and
-// wave-uniform), and [lo, end) is staged but not yet written.  Complete lines
-// leave as 16-byte stores; the bytes before the run's first line boundary and,
-// with `last`, those after its last one leave element by element; an unfinished
-// line at the end otherwise stays behind and is moved to the front of the slice,
-// where the next step continues it.  So a wave writes two partial lines per
-// tile instead of two per step: partial-line writes cost the memory system about
-// as much as whole lines.  Returns nothing; updates gline, lo and end.
+// A dword of a wave's LDS queue at any offset that is a multiple of W (with
+// 16-bit elements the queue need not sit at the destination's offset modulo 4).
 template <int W>
-__device__ inline void wave_flush_lines(unsigned char*& gline, unsigned char* stage, unsigned& lo,
-                                        unsigned& end, bool last, int lane) {
-    const unsigned first_line = (lo + 127u) >> 7;
-    const unsigned last_line = end >> 7;
-    if (!last && last_line < first_line + ((lo & 127u) != 0u ? 0u : 1u)) return;   // no line completed yet
-    // the run's head: from lo to its first line boundary
-    const unsigned head_end = min(end, first_line << 7);
-    if (lo + W * lane < head_end) {
-        const unsigned o = lo + W * lane;
-        if (W == 4)
-            *reinterpret_cast<unsigned*>(gline + o) = *reinterpret_cast<const unsigned*>(stage + o);
-        else
-            *reinterpret_cast<unsigned short*>(gline + o) = *reinterpret_cast<const unsigned short*>(stage + o);
+__device__ inline unsigned queue_dword(const unsigned char* p) {
+    if (W == 4) return *reinterpret_cast<const unsigned*>(p);
+    return static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(p)) |
+           (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(p + 2)) << 16);
+}
+
+// Writes out what a wave has staged so far.  The wave's packed run goes through
+// its LDS slice like through a queue: slice offset p holds the byte that belongs
+// at global address gzero + p (gzero is wave-uniform and a multiple of W; nothing
+// before offset lo is ever dereferenced), and [lo, end) is staged but not yet
+// written.  Every store instruction covers one 256-byte aligned block of the
+// destination, a dword per lane, so whole 128-byte lines leave as whole lines
+// wherever the run begins (partial-line writes cost the memory system about as
+// much as whole lines).  Unless `last`, the bytes after the run's last line
+// boundary stay behind: they move to the front of the slice, where the next
+// step continues them, so a wave writes two partial lines per tile, not two per
+// step.  Updates gzero, lo and end.
+template <int W>
+__device__ inline void wave_flush(unsigned char*& gzero, unsigned char* stage, unsigned& lo,
+                                  unsigned& end, bool last, int lane) {
+    const uintptr_t g = reinterpret_cast<uintptr_t>(gzero);
+    // slice offsets of the bytes to write: [first, tail)
+    int first = static_cast<int>(lo);
+    const int keep_back = last ? 0 : static_cast<int>((g + end) & 127u);   // bytes after the last line boundary
+    const int tail = static_cast<int>(end) - keep_back;
+    if (tail <= first) {       // no line completed yet (or, with `last`, nothing staged)
+        if (last) lo = end;
+        return;
     }
-    // whole lines
-    for (unsigned q = (first_line << 3) + lane; q < (last_line << 3); q += kWaveSize)
-        store16_stream(gline + q * 16u, *reinterpret_cast<const uint4*>(stage + q * 16u));
-    const unsigned tail_begin = max(head_end, last_line << 7);
-    if (last) {
-        const unsigned o = tail_begin + W * lane;
-        if (o < end) {
-            if (W == 4)
-                *reinterpret_cast<unsigned*>(gline + o) = *reinterpret_cast<const unsigned*>(stage + o);
-            else
-                *reinterpret_cast<unsigned short*>(gline + o) = *reinterpret_cast<const unsigned short*>(stage + o);
+    int stop = tail;
+    if (W == 2) {
+        // odd halves at either end, so that what is left is whole dwords of the destination
+        if ((g + first) & 2u) {
+            if (lane == 0)
+                *reinterpret_cast<unsigned short*>(gzero + first) =
+                    *reinterpret_cast<const unsigned short*>(stage + first);
+            first += 2;
         }
+        if (((g + stop) & 2u) && stop > first) {
+            if (lane == 0)
+                *reinterpret_cast<unsigned short*>(gzero + (stop - 2)) =
+                    *reinterpret_cast<const unsigned short*>(stage + (stop - 2));
+            stop -= 2;
+        }
+    }
+    // one 256-byte aligned block of the destination per store instruction
+    for (int block = first - static_cast<int>((g + first) & 255u); block < stop; block += 256) {
+        const int at = block + 4 * lane;
+        if (at >= first && at < stop)
+            __builtin_nontemporal_store(queue_dword<W>(stage + at),
+                                        reinterpret_cast<unsigned*>(gzero + block) + lane);
+    }
+    if (last) {
         lo = end;
         return;
     }
-    // the unfinished line moves to the front of the slice (source and destination do not overlap:
-    // a line was completed, so tail_begin >= 128)
-    const unsigned rem = end - tail_begin;
+    // the unfinished line moves to the front of the slice (all lanes read before any writes:
+    // source and destination may overlap)
+    const unsigned rem = static_cast<unsigned>(keep_back);          // below 128
     unsigned keep = 0;
     const bool mine = static_cast<unsigned>(W * lane) < rem;
     if (mine) {
-        if (W == 4) keep = *reinterpret_cast<const unsigned*>(stage + tail_begin + W * lane);
-        else keep = *reinterpret_cast<const unsigned short*>(stage + tail_begin + W * lane);
+        if (W == 4) keep = *reinterpret_cast<const unsigned*>(stage + tail + W * lane);
+        else keep = *reinterpret_cast<const unsigned short*>(stage + tail + W * lane);
     }
     wave_lds_sync();
     if (mine) {
         if (W == 4) *reinterpret_cast<unsigned*>(stage + W * lane) = keep;
         else *reinterpret_cast<unsigned short*>(stage + W * lane) = static_cast<unsigned short>(keep);
     }
-    gline += tail_begin;
+    gzero += tail;
     lo = 0;
     end = rem;
 }
@@ -380,15 +433,14 @@ __device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetch
 
 // Device-wide exclusive scan of the per-tile counts, single pass (the paper's
 // "offset to the next mask", section 5.1, for a whole tile at a time).
-// Called by one whole wave of the tile's workgroup.  Returns the number of
-// kept elements in all tiles before `tile`.
 //
-// Protocol.  Every tile publishes its own count.  Tile 64b+63 also publishes
-// the running total up to and including itself (one prefix per block of 64
-// tiles).  A tile finds the nearest published block prefix behind it and adds
-// the counts of the tiles between that block and itself, two counts per 8-byte
-// load across the wave.  In steady state that is a few hundred counts and the
-// walk takes one pass.
+// Protocol.  Every tile publishes its own count (the wave of the tile that
+// finishes its zero tests last does).  Tile 64b+63 also publishes the running
+// total up to and including itself (one prefix per block of 64 tiles).  A tile
+// finds the nearest published block prefix behind it and adds the counts of the
+// tiles between that block and itself, two counts per 8-byte load across the
+// wave.  In steady state that is a few hundred counts and the walk takes one
+// pass.
 //
 // Why this shape (measured on MI355X): a device-scope load of a line that other
 // XCDs are still writing costs a coherence round trip and slows the streaming
@@ -405,81 +457,87 @@ __device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetch
 // polls the waiting wave computes a missing predecessor's count itself
 // (`count_tile`, a re-read of that tile's input) and publishes it, so the walk
 // ends whatever the dispatch order.
+//
+// The walk is split in two so that its first memory round trip costs the tile
+// nothing: scan_request_prefixes() is called when the tile starts (the prefix
+// found then is a few blocks further back than one found later would be: a few
+// more counts to add), scan_exclusive_prefix() when the tile's own zero tests
+// are done.  Both are called by one whole wave of the tile.
+__device__ inline unsigned long long scan_request_prefixes(const unsigned long long* prefixes,
+                                                           unsigned tile, int lane) {
+    const int idx = static_cast<int>(tile) / kBlockTiles - 1 - lane;
+    return idx >= 0 ? load64(prefixes + idx) : kPrefixValid;   // before block 0 the prefix is 0
+}
+
+// Returns the number of kept elements in all tiles before `tile` (not 0);
+// `requested` is what scan_request_prefixes() returned to this lane.
 template <class CountTile>
-__device__ inline unsigned long long tile_exclusive_prefix(unsigned* counts,
-                                                           unsigned long long* prefixes,
-                                                           unsigned tile, unsigned count, int lane,
+__device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
+                                                           const unsigned long long* prefixes,
+                                                           unsigned long long requested,
+                                                           unsigned tile, int lane,
                                                            unsigned patience, WsHeader* hdr,
                                                            const CountTile& count_tile) {
-    if (lane == 0) store32(counts + tile, kCountValid | count);
-    unsigned long long exclusive = 0;
-    if (tile != 0) {
-        const int t = static_cast<int>(tile);
-        // nearest published block prefix; before block 0 the prefix is 0
-        int bb = t / kBlockTiles - 1;
-        unsigned long long base = 0;
-        int lo = 0;
-        while (true) {
-            const int idx = bb - lane;
-            const unsigned long long pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;
-            const unsigned long long have = __ballot((pv & kPrefixValid) != 0);
-            if (have) {
-                const int k = __ffsll(static_cast<long long>(have)) - 1;
-                base = __shfl(pv, k) & ~kPrefixValid;
-                lo = (bb - k + 1) * kBlockTiles;   // first tile after that block
-                break;
-            }
-            bb -= kWaveSize;
+    const int t = static_cast<int>(tile);
+    // nearest published block prefix
+    int bb = t / kBlockTiles - 1;
+    unsigned long long base = 0;
+    int lo = 0;
+    unsigned long long pv = requested;
+    while (true) {
+        const unsigned long long have = __ballot((pv & kPrefixValid) != 0);
+        if (have) {
+            const int k = __ffsll(static_cast<long long>(have)) - 1;
+            base = __shfl(pv, k) & ~kPrefixValid;
+            lo = (bb - k + 1) * kBlockTiles;   // first tile after that block
+            break;
         }
-        // Counts of tiles lo .. t-1, a pair per 8-byte load (lo is a multiple of 64:
-        // pairs are aligned).  A lane adds up its pairs in order as far as they are
-        // published; a later round asks again only for what was missing, so the
-        // waiting re-reads no more than the newest lines of counts.
-        int next = lo + 2 * lane;      // the lane's first pair not added yet
-        unsigned sum = 0;              // a lane adds few counts, each below 2^16
-        unsigned polls = 0;
-        while (true) {
-            int hole = -1;
-#pragma unroll 1
-            for (int i = next; i < t; i += 2 * kWaveSize) {
-                const unsigned long long pair =
-                    load64(reinterpret_cast<const unsigned long long*>(counts + i));
-                const unsigned c0 = static_cast<unsigned>(pair);
-                const unsigned c1 = i + 1 < t ? static_cast<unsigned>(pair >> 32) : kCountValid;
-                if (hole >= 0) continue;
-                if (c0 & c1 & kCountValid) {
-                    sum += (c0 & ~kCountValid) + (c1 & ~kCountValid);
-                    next = i + 2 * kWaveSize;
-                } else {
-                    hole = (c0 & kCountValid) ? i + 1 : i;
-                }
-            }
-            const unsigned long long holes = __ballot(hole >= 0);
-            if (!holes) {
-                exclusive = base + wave_sum(static_cast<unsigned long long>(sum));
-                break;
-            }
-            if (polls < patience) {
-                ++polls;
-                __builtin_amdgcn_s_sleep(kPollSleep);
-                continue;
-            }
-            // help one unpublished predecessor, then look again without waiting anew
-            const int hole_lane = __ffsll(static_cast<long long>(holes)) - 1;
-            const int q = __shfl(hole, hole_lane);
-            const unsigned helped_count = count_tile(static_cast<unsigned>(q), lane);
-            unsigned old = 0;
-            if (lane == 0) {
-                old = atomicMax(counts + q, kCountValid | helped_count);  // same value as the owner's
-                atomicAdd(&hdr->helped, 1ull);
-            }
-            // the atomic has returned, so it has been performed before any lane polls again
-            asm volatile("" : : "v"(old) : "memory");
-        }
+        bb -= kWaveSize;
+        const int idx = bb - lane;
+        pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;
     }
-    if (tile % kBlockTiles == kBlockTiles - 1 && lane == 0)
-        store64(prefixes + tile / kBlockTiles, kPrefixValid | (exclusive + count));
-    return exclusive;
+    // Counts of tiles lo .. t-1, a pair per 8-byte load (lo is a multiple of 64:
+    // pairs are aligned).  A lane adds up its pairs in order as far as they are
+    // published; a later round asks again only for what was missing, so the
+    // waiting re-reads no more than the newest lines of counts.
+    int next = lo + 2 * lane;      // the lane's first pair not added yet
+    unsigned sum = 0;              // a lane adds few counts, each below 2^16
+    unsigned polls = 0;
+    while (true) {
+        int hole = -1;
+#pragma unroll 1
+        for (int i = next; i < t; i += 2 * kWaveSize) {
+            const unsigned long long pair =
+                load64(reinterpret_cast<const unsigned long long*>(counts + i));
+            const unsigned c0 = static_cast<unsigned>(pair);
+            const unsigned c1 = i + 1 < t ? static_cast<unsigned>(pair >> 32) : kCountValid;
+            if (hole >= 0) continue;
+            if (c0 & c1 & kCountValid) {
+                sum += (c0 & ~kCountValid) + (c1 & ~kCountValid);
+                next = i + 2 * kWaveSize;
+            } else {
+                hole = (c0 & kCountValid) ? i + 1 : i;
+            }
+        }
+        const unsigned long long holes = __ballot(hole >= 0);
+        if (!holes) return base + wave_sum(static_cast<unsigned long long>(sum));
+        if (polls < patience) {
+            ++polls;
+            __builtin_amdgcn_s_sleep(kPollSleep);
+            continue;
+        }
+        // help one unpublished predecessor, then look again without waiting anew
+        const int hole_lane = __ffsll(static_cast<long long>(holes)) - 1;
+        const int q = __shfl(hole, hole_lane);
+        const unsigned helped_count = count_tile(static_cast<unsigned>(q), lane);
+        unsigned old = 0;
+        if (lane == 0) {
+            old = atomicMax(counts + q, kCountValid | helped_count);  // same value as the owner's
+            atomicAdd(&hdr->helped, 1ull);
+        }
+        // the atomic has returned, so it has been performed before any lane polls again
+        asm volatile("" : : "v"(old) : "memory");
+    }
 }
 
 // Encoder clean-up, see WsHeader::finish.  finish_arrive() is called by lane 0
@@ -511,21 +569,109 @@ __device__ inline void finish_call(WsHeader* hdr, unsigned* counts, unsigned num
     hdr->finish[lane].value = 0u;
 }
 
+// ------------------------------------------------- encoder: loads and zero tests
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+__device__ inline unsigned load_stream(const unsigned* p) { return __builtin_nontemporal_load(p); }
+__device__ inline unsigned load_stream(const unsigned short* p) { return __builtin_nontemporal_load(p); }
+
+// Dword d of a tensor that is wholly inside it.  SPLIT: 16-bit elements at an
+// address that is not a multiple of 4 are fetched as two halves.
+template <bool SPLIT>
+__device__ __forceinline__ unsigned load_dword(const unsigned char* in, size_t d) {
+    if (SPLIT) {
+        const unsigned short* p = reinterpret_cast<const unsigned short*>(in) + 2 * d;
+        return static_cast<unsigned>(load_stream(p)) | (static_cast<unsigned>(load_stream(p + 1)) << 16);
+    }
+    return load_stream(reinterpret_cast<const unsigned*>(in) + d);
+}
+
+// Dword `index` of a run of dwords that starts at `base` (wave-uniform, inside
+// the tensor) and of which only dwords 0 .. room belong to the tensor, the last
+// one maybe only with its low half (half_tail: 16-bit elements, odd count).
+// What lies past the tensor reads as zero.  The dword that holds the tensor's
+// last element is loaded whole (an aligned dword never straddles a page, so
+// that is as safe as loading the element) and later lanes are redirected to
+// it, so the loads need no branch; the excess is cleared in registers.  SPLIT
+// fetches halves and checks each.
+template <bool SPLIT>
+__device__ __forceinline__ unsigned load_dword_ragged(const unsigned char* base, unsigned index,
+                                                      unsigned room, bool half_tail) {
+    if (SPLIT) {
+        const unsigned short* p = reinterpret_cast<const unsigned short*>(base);
+        const unsigned lo = index <= room ? static_cast<unsigned>(load_stream(p + 2 * index)) : 0u;
+        const unsigned hi = index < room || (index == room && !half_tail)
+                                ? static_cast<unsigned>(load_stream(p + 2 * index + 1)) : 0u;
+        return lo | (hi << 16);
+    }
+    unsigned x = load_stream(reinterpret_cast<const unsigned*>(base) + (index < room ? index : room));
+    if (index > room) x = 0u;
+    if (half_tail && index == room) x &= 0xFFFFu;
+    return x;
+}
+
+// Which elements are kept.  Plain ZVC (RELU = false) keeps the elements that are
+// non-zero as integers (section 5.2: words compared to zero form the mask
+// bits).  The fused ReLU + ZVC encoder (RELU = true) reads pre-activation
+// values (IEEE-style, sign in the top bit: fp32, fp16, bf16) and keeps those
+// whose sign bit is clear and which are not +0, i.e. the non-zeros of ReLU(x);
+// as signed integers those are exactly the words greater than zero.
+// kept_first: the element in the dword's low W bytes; kept_second (16-bit
+// elements only): the one in its high half.
+template <int W, bool RELU>
+__device__ inline bool kept_first(unsigned x) {
+    if (W == 4) return RELU ? static_cast<int>(x) > 0 : x != 0u;
+    const unsigned low = x & 0xFFFFu;
+    return RELU ? (low - 1u) < 0x7FFFu : low != 0u;
+}
+template <bool RELU>
+__device__ inline bool kept_second(unsigned x) {
+    return RELU ? static_cast<int>(x) > 0xFFFF : x > 0xFFFFu;
+}
+
+// Bits of `even` and `odd` interleaved: bit 2i of the result is bit i of even,
+// bit 2i+1 is bit i of odd (wave-uniform operands, scalar unit).  With 16-bit
+// elements a lane holds two neighbours, so the ballots of the first and of the
+// second elements zip into the masks.
+__device__ inline unsigned long long zip_bits(unsigned even, unsigned odd) {
+    unsigned long long e, o;
+    asm("s_bitreplicate_b64_b32 %0, %1" : "=s"(e) : "s"(even));
+    asm("s_bitreplicate_b64_b32 %0, %1" : "=s"(o) : "s"(odd));
+    return (e & 0x5555555555555555ull) | (o & 0xAAAAAAAAAAAAAAAAull);
+}
+
+// v in lane LANE := the wave-uniform value s (other lanes keep theirs).  The
+// value usually comes straight from a vector compare; a vector instruction that
+// reads such a freshly written scalar as an operand needs one wait state, which
+// the compiler cannot know for an instruction it does not see, hence the s_nop.
+template <int LANE>
+__device__ __forceinline__ void set_lane(unsigned& v, unsigned s) {
+    asm("s_nop 0\n\tv_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(LANE));
+}
+
 // Count of kept elements of input tile q, by one wave (scan self-help).
-template <int W, int LOADS, bool ALIGNED, bool RELU>
+template <int W, int CH, bool RELU, bool SPLIT>
 struct CountInputTile {
     const unsigned char* in;
     size_t n;
     __device__ unsigned operator()(unsigned q, int lane) const {
-        constexpr int E = 16 / W;
-        constexpr int kTileElems = kThreads * LOADS * E;
-        const size_t e0 = static_cast<size_t>(q) * kTileElems;
+        constexpr unsigned kTileDwords = EncoderGeometry<W, CH>::kTileBytes / 4;
+        const size_t d0 = static_cast<size_t>(q) * kTileDwords;      // inside the tensor: q is a predecessor
+        const size_t last = (n * W - 1) / 4;
+        const unsigned room = last - d0 < kTileDwords ? static_cast<unsigned>(last - d0) : kTileDwords;
+        const bool half_tail = W == 2 && (n & 1u) != 0u && room < kTileDwords;
         unsigned long long count = 0;
 #pragma unroll 1
-        for (int i = 0; i < LOADS * kWaves; ++i) {
-            const uint4 v = load_chunk<W, ALIGNED>(
-                in, e0 + (static_cast<size_t>(i) * kWaveSize + lane) * E, n);
-            count += __popc(presence_bits<W, RELU>(v));
+        for (unsigned i = 0; i < kTileDwords; i += kWaveSize) {
+            const unsigned x = load_dword_ragged<SPLIT>(in + d0 * 4, i + lane, room, half_tail);
+            count += kept_first<W, RELU>(x) ? 1u : 0u;
+            if (W == 2) count += kept_second<RELU>(x) ? 1u : 0u;
         }
         return static_cast<unsigned>(wave_sum(count));
     }
@@ -565,78 +711,48 @@ struct EncoderArgs {
     unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
 };
 
-// The tile that holds the end of the tensor.  Aligned tensors: every lane loads
-// a whole 16-byte chunk without a branch -- chunks past the last one that holds
-// an element are redirected to that one (an aligned chunk that holds an element
-// lies within the tensor's pages) -- and what is past the end is cleared in
-// registers afterwards, so the loads go out back to back like a whole tile's.
-template <int W, int LOADS, bool ALIGNED>
-__device__ __forceinline__ void load_ragged_tile(uint4 (&data)[LOADS], const EncoderArgs& a,
-                                                 size_t tile_elem0, int wave, int lane) {
-    constexpr int E = 16 / W;
-    if (ALIGNED) {
-        const size_t last_chunk = (a.n - 1) / E;
-        const size_t chunk0 = tile_elem0 / E + static_cast<size_t>(wave) * LOADS * kWaveSize + lane;
-        const uint4* in16 = reinterpret_cast<const uint4*>(a.in);
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const size_t q = chunk0 + static_cast<size_t>(j) * kWaveSize;
-            data[j] = load16_stream(in16 + (q < last_chunk ? q : last_chunk));
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        const unsigned last_bytes = static_cast<unsigned>(a.n - last_chunk * E) * W;   // 1 .. 16
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const size_t q = chunk0 + static_cast<size_t>(j) * kWaveSize;
-            if (q < last_chunk) continue;
-            const unsigned valid_bytes = q == last_chunk ? last_bytes : 0u;
-            const unsigned raw[4] = {data[j].x, data[j].y, data[j].z, data[j].w};
-            unsigned d[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const unsigned lo = 4u * k;
-                d[k] = valid_bytes >= lo + 4u ? raw[k]
-                     : valid_bytes > lo      ? raw[k] & ((1u << (8u * (valid_bytes - lo))) - 1u)
-                                             : 0u;
-            }
-            data[j] = make_uint4(d[0], d[1], d[2], d[3]);
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const size_t e0 = tile_elem0 + (static_cast<size_t>(wave * LOADS + j) * kWaveSize + lane) * E;
-            data[j] = load_chunk<W, false>(a.in, e0, a.n);
-        }
-    }
-}
-
 // Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.  With
 // RELU the input is the pre-activation tensor and the stream is that of
 // ReLU(input): the dense ReLU output is never written or read.
 //
+// A wave owns CH consecutive chunks of the tile (256 bytes each, a dword per
+// lane).  Its work, in the order in which it happens:
+//
+//   1. zero tests as the loads arrive: the ballot of a chunk's test is two
+//      masks (fp32) or, zipped with the ballot of the lanes' second elements,
+//      four (16-bit); its popcount adds to the wave's total.  The masks are
+//      gathered into registers lane by lane and leave as coalesced stores.
+//   2. the wave adds its total to the tile's arrival word in LDS; the wave that
+//      arrives last publishes the tile's count for the tiles behind it, at once.
+//   3. the wave stages its kept elements in its LDS queue in packed order
+//      (position = ballot bits in lower lanes + kept elements of earlier
+//      chunks), as many steps as the queue holds: that needs nothing from other
+//      tiles, and it gives the tiles in front the time to publish their counts.
+//   4. wave 0 finishes the device-wide scan (its first round trip has been
+//      under way since the tile started); one barrier hands the result to the
+//      other waves.
+//   5. every wave writes its queue out in whole lines (wave_flush), staging
+//      whatever did not fit before.
+//
 // WINDOWED selects the paper's own stream order (section 5.1: a group's
 // non-zeros are appended right after its mask) in windows of 1 KB of input,
 // packed back to back, plus a table with the byte offset of every window.  A
-// window is one load of a wave and a wave stages four of them at a time, so the
-// only differences are where things go in the wave's LDS slice -- the mask of
-// group g of the step sits before the group's elements, i.e. after g masks and
-// all earlier kept elements -- and that masks leave with the values instead of
-// going to a mask area.  The scan is the same: a window's byte offset is
-// 4 x (groups before it) + W x (kept elements before it).
-// (The second launch bound asks for six waves per SIMD at 32 KB tiles: the
-// kernel needs 82 VGPRs there when left alone, two more than six waves allow,
-// and fits in 80 without spilling.)
-template <int W, int LOADS, bool ALIGNED, bool RELU, bool WINDOWED>
-__global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(EncoderArgs a) {
-    using G = Geometry<W, LOADS>;
-    constexpr int E = G::kElemsPerLane;
-    constexpr int LPG = G::kLanesPerGroup;
-    constexpr int kStepGroups = kStageLoads * G::kGroupsPerLoad;   // masks of one window: 32 | 64
-    constexpr int kMaskUnits = 4 / W;                                    // a mask in units of W bytes
+// window is four chunks, so the only differences are where things go in the
+// wave's queue -- a group's mask sits before the group's elements -- and that
+// masks leave with the values instead of going to a mask area.  The scan is the
+// same: a window's byte offset is 4 x (groups before it) + W x (kept elements
+// before it).
+template <int W, int CH, bool RELU, bool WINDOWED, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
+    using G = EncoderGeometry<W, CH>;
+    constexpr int CG = G::kChunkGroups;
+    constexpr int kAhead = CH < 32 ? CH : 32;     // loads a wave keeps in flight: 8 KB
+    constexpr int kWindowChunks = 4;              // a window of the windowed stream: 1 KB of input
+    static_assert(W == 2 || !SPLIT, "only 16-bit elements can sit at an odd half dword");
 
-    __shared__ __align__(16) unsigned char
-        s_stage[kWaves][G::kWaveStageBytes + (WINDOWED ? 4 * kStepGroups : 0) + 128];
+    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kQueueBytes];
     __shared__ unsigned s_wave_total[kWaves];
+    __shared__ unsigned s_arrive;                 // waves arrived << 24 | kept elements so far
     __shared__ unsigned long long s_prefix;
 
     const int tid = threadIdx.x;
@@ -644,100 +760,197 @@ __global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
     ZVC_TRACE_POINT(tile, 0);
+    if (tid == 0) s_arrive = 0u;
 
-    uint4 cur[LOADS];
+    // the scan's first round trip starts now and is looked at after the zero tests
+    unsigned long long requested = 0;
+    if (wave == 0 && tile != 0) requested = scan_request_prefixes(a.prefixes, tile, lane);
 
-    // ---- zero test, in-wave ranks (section 5.2: prefix sum over the mask bits), masks
-    unsigned below16[LOADS / 2];     // kept elements of lower lanes in the same load, 16 bits each
-    unsigned run[LOADS + 1];         // wave-uniform: kept elements of the wave's earlier loads
-    unsigned my_mask[G::kMaskRegs];
+    const size_t wave_elem0 = static_cast<size_t>(tile) * G::kTileElems + static_cast<size_t>(wave) * G::kWaveElems;
+    const size_t wave_group0 = static_cast<size_t>(tile) * G::kTileGroups + static_cast<size_t>(wave) * G::kWaveGroups;
+    const size_t wave_dword0 = wave_elem0 / (4 / W);
+
+    // ---- 1. loads, zero tests, masks (section 5.2: words compared to zero form the mask bits)
+    unsigned cur[CH];
+    unsigned mask_reg[G::kMaskRegs];
+    unsigned step_total[G::kSteps];               // wave-uniform
 #pragma unroll
-    for (int k = 0; k < LOADS / 2; ++k) below16[k] = 0;
-    run[0] = 0;
-    const int lane_in_group = lane % LPG;
-    const unsigned field_shift = static_cast<unsigned>(E * lane_in_group);
-    const auto zero_tests = [&](const auto& after_load) __attribute__((always_inline)) {
-    #pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            unsigned bits = 0, below = 0, load_total = 0;
-    #pragma unroll
-            for (int c = 0; c < E; ++c) {
-                const bool nz = element_kept<W, RELU>(cur[j], c);
-                const unsigned long long b = __ballot(nz);
-                below = lanes_below(b, below);
-                load_total += static_cast<unsigned>(__popcll(b));
-                bits |= (nz ? 1u : 0u) << c;
-            }
-            // Pin the rank and the total here and keep the loads' code apart (below).
-            // Left alone the compiler postpones the mbcnt chains until the compaction,
-            // or hoists the compares of all loads, and keeps every ballot of the tile
-            // alive at once, which costs two lane-spills per ballot.
-            below16[j / 2] |= below << (16 * (j % 2));
-            asm volatile("" : "+v"(below16[j / 2]), "+s"(load_total));
-            run[j + 1] = run[j] + load_total;
-            // the group's mask: OR of the lanes' bit fields, each at its position
-            // (the windowed layout forms it again when it stages the load: keeping
-            // it in registers through the scan costs the 64 KB tile a wave of occupancy)
+    for (int r = 0; r < G::kMaskRegs; ++r) mask_reg[r] = 0u;
+#pragma unroll
+    for (int h = 0; h < G::kSteps; ++h) step_total[h] = 0u;
+
+    const auto zero_test = [&](auto kc) __attribute__((always_inline)) {
+        constexpr int k = decltype(kc)::value;
+        const unsigned x = cur[k];
+        if constexpr (W == 4) {
+            const unsigned long long b = __ballot(kept_first<4, RELU>(x));
+            step_total[k / kStepChunks] += static_cast<unsigned>(__popcll(b));
             if (!WINDOWED) {
-                const unsigned m = group_or<LPG>(bits << field_shift);
-                if (lane_in_group == j % LPG) my_mask[j / LPG] = m;
+                set_lane<(2 * k) % kWaveSize>(mask_reg[(2 * k) / kWaveSize], static_cast<unsigned>(b));
+                set_lane<(2 * k + 1) % kWaveSize>(mask_reg[(2 * k + 1) / kWaveSize], static_cast<unsigned>(b >> 32));
             }
-            after_load(j);
-            __builtin_amdgcn_sched_barrier(0);
-            if (j == 0) ZVC_TRACE_POINT(tile, 1);
+        } else {
+            const unsigned long long be = __ballot(kept_first<2, RELU>(x));
+            const unsigned long long bo = __ballot(kept_second<RELU>(x));
+            step_total[k / kStepChunks] += static_cast<unsigned>(__popcll(be)) + static_cast<unsigned>(__popcll(bo));
+            if (!WINDOWED) {
+                const unsigned long long z0 = zip_bits(static_cast<unsigned>(be), static_cast<unsigned>(bo));
+                const unsigned long long z1 = zip_bits(static_cast<unsigned>(be >> 32), static_cast<unsigned>(bo >> 32));
+                set_lane<(4 * k) % kWaveSize>(mask_reg[(4 * k) / kWaveSize], static_cast<unsigned>(z0));
+                set_lane<(4 * k + 1) % kWaveSize>(mask_reg[(4 * k + 1) / kWaveSize], static_cast<unsigned>(z0 >> 32));
+                set_lane<(4 * k + 2) % kWaveSize>(mask_reg[(4 * k + 2) / kWaveSize], static_cast<unsigned>(z1));
+                set_lane<(4 * k + 3) % kWaveSize>(mask_reg[(4 * k + 3) / kWaveSize], static_cast<unsigned>(z1 >> 32));
+            }
         }
+        if (k == 0) ZVC_TRACE_POINT(tile, 1);
     };
-    // A tile that lies wholly inside an aligned tensor needs no bounds checks
-    // (LOADS x 16 bytes per lane, 1 KB per wave instruction).  It has its own copy
-    // of the zero tests: after a join with the ragged path the compiler would wait
-    // for all the tile's loads before the first test; on its own it tests each
-    // load as it arrives.  A wave keeps kLoadsAhead loads in flight and asks for
-    // the next one after each test: an L1 cache has only some 8 KB of requests in
-    // flight at a time, and whatever else a CU's waves have queued stands in the way
-    // of the scan's and the stores' traffic (all 16 at once: 1-2 % slower on large
-    // tensors; 4: slower again).
-    const size_t tile_elem0 = static_cast<size_t>(tile) * G::kTileElems;
-    if (ALIGNED && tile_elem0 + G::kTileElems <= a.n) {
-        constexpr int kLoadsAhead = LOADS < 8 ? LOADS : 8;
-        const uint4* wave_base = reinterpret_cast<const uint4*>(a.in + tile_elem0 * W) +
-                                 static_cast<size_t>(wave) * LOADS * kWaveSize;
-#pragma unroll
-        for (int j = 0; j < kLoadsAhead; ++j) {
-            cur[j] = load16_stream(wave_base + j * kWaveSize + lane);
+
+    // A wave that lies wholly inside the tensor needs no bounds checks: it keeps
+    // kAhead loads in flight and tests each chunk as it arrives.  The barrier makes
+    // the cleared arrival word visible to the tile's waves; it comes after the
+    // first loads have been issued, so it costs them nothing.
+    if (wave_elem0 + G::kWaveElems <= a.n) {
+        static_for<0, kAhead>([&](auto kc) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc)::value;
+            cur[k] = load_dword<SPLIT>(a.in, wave_dword0 + static_cast<size_t>(k) * kWaveSize + lane);
             __builtin_amdgcn_sched_barrier(0);   // in the order in which the tests use them
-        }
-        zero_tests([&](int j) __attribute__((always_inline)) {
-            if (j + kLoadsAhead < LOADS)
-                cur[(j + kLoadsAhead) % LOADS] =
-                    load16_stream(wave_base + (j + kLoadsAhead) * kWaveSize + lane);
+        });
+        lds_barrier();
+        static_for<0, CH>([&](auto kc) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc)::value;
+            zero_test(kc);
+            if constexpr (k + kAhead < CH)
+                cur[k + kAhead] =
+                    load_dword<SPLIT>(a.in, wave_dword0 + static_cast<size_t>(k + kAhead) * kWaveSize + lane);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    } else if (wave_elem0 < a.n) {
+        // the wave that holds the tensor's end
+        const size_t last = (a.n * W - 1) / 4;                       // last dword with an element in it
+        const unsigned room = static_cast<unsigned>(last - wave_dword0);
+        const bool half_tail = W == 2 && (a.n & 1u) != 0u;
+        const unsigned char* base = a.in + wave_dword0 * 4;
+        static_for<0, CH>([&](auto kc) __attribute__((always_inline)) {
+            constexpr int k = decltype(kc)::value;
+            cur[k] = load_dword_ragged<SPLIT>(base, static_cast<unsigned>(k * kWaveSize + lane), room, half_tail);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        lds_barrier();
+        static_for<0, CH>([&](auto kc) __attribute__((always_inline)) {
+            zero_test(kc);
+            __builtin_amdgcn_sched_barrier(0);
         });
     } else {
-        load_ragged_tile<W, LOADS, ALIGNED>(cur, a, tile_elem0, wave, lane);
-        zero_tests([](int) {});
+        // past the tensor's end: nothing kept, no masks (the wave still takes part in the tile's protocol)
+#pragma unroll
+        for (int k = 0; k < CH; ++k) cur[k] = 0u;
+        lds_barrier();
     }
     ZVC_TRACE_POINT(tile, 2);
-    // The compaction tests the elements again.  Hide from the compiler that it
-    // has compared these registers before: it would keep all the ballots for
-    // later, which costs more (lane-spills) than the second compare.
+    unsigned wave_total = 0;
 #pragma unroll
-    for (int j = 0; j < LOADS; ++j)
-        asm volatile("" : "+v"(cur[j].x), "+v"(cur[j].y), "+v"(cur[j].z), "+v"(cur[j].w));
+    for (int h = 0; h < G::kSteps; ++h) wave_total += step_total[h];
+
+    // ---- 2. arrival: the last wave of the tile to get here publishes the tile's count
+    unsigned arrived = 0;
+    if (lane == 0) {
+        s_wave_total[wave] = wave_total;
+        arrived = __hip_atomic_fetch_add(&s_arrive, (1u << 24) | wave_total, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    arrived = uniform(arrived);
+    const bool publisher = (arrived >> 24) == kWaves - 1;
+    if (publisher && lane == 0)
+        store32(a.counts + tile, kCountValid | ((arrived & 0xFFFFFFu) + wave_total));
+
     if (!WINDOWED) {
 #pragma unroll
-        for (int q = 0; q < G::kMaskRegs; ++q) {
-            const int j = q * LPG + lane_in_group;  // the load whose mask this lane kept
-            if (j < LOADS) {
-                const size_t g = static_cast<size_t>(tile) * G::kTileGroups +
-                                 static_cast<size_t>(wave * LOADS + j) * G::kGroupsPerLoad +
-                                 lane / LPG;
-                if (g < a.num_groups) __builtin_nontemporal_store(my_mask[q], a.masks + g);
-            }
+        for (int r = 0; r < G::kMaskRegs; ++r) {
+            const size_t g = wave_group0 + static_cast<size_t>(r) * kWaveSize + lane;
+            if (r * kWaveSize + lane < G::kWaveGroups && g < a.num_groups)
+                __builtin_nontemporal_store(mask_reg[r], a.masks + g);
         }
     }
-    // ---- tile-level scan of the wave totals
-    if (lane == 0) s_wave_total[wave] = run[LOADS];
-    lds_barrier();
+
+    // ---- 3./5. compaction (section 5.2: shift non-zeros to their packed slots)
+    unsigned char* stage = s_stage[wave];
+    unsigned q_lo = 0, q_end = 0;                 // the wave's queue: slice offsets, wave-uniform
+    unsigned zero_local = 0;                      // offset within the wave's run of slice offset 0
+    unsigned window_local = 0;                    // lane i: offset within the wave's run of its window i
+    // groups of the tensor in chunk k of this wave: CG, fewer where the tensor ends
+    const auto groups_from = [&](int first_group, int count) -> unsigned {
+        const size_t g = wave_group0 + static_cast<size_t>(first_group);
+        return g >= a.num_groups ? 0u
+             : a.num_groups - g < static_cast<size_t>(count) ? static_cast<unsigned>(a.num_groups - g)
+                                                             : static_cast<unsigned>(count);
+    };
+    const auto step_bytes = [&](int h) -> unsigned {
+        return step_total[h] * W + (WINDOWED ? 4u * groups_from(h * G::kStepGroups, G::kStepGroups) : 0u);
+    };
+    const auto stage_step = [&](auto hc) __attribute__((always_inline)) {
+        constexpr int h = decltype(hc)::value;
+        static_for<0, kStepChunks>([&](auto jc) __attribute__((always_inline)) {
+            constexpr int k = h * kStepChunks + decltype(jc)::value;
+            const unsigned x = cur[k];
+            const unsigned chunk_groups = WINDOWED ? groups_from(k * CG, CG) : 0u;
+            if (WINDOWED && k % kWindowChunks == 0)
+                set_lane<k / kWindowChunks>(window_local, zero_local + q_end);
+            if constexpr (W == 4) {
+                const bool keep = kept_first<4, RELU>(x);
+                const unsigned long long b = __ballot(keep);
+                // windowed: the lane's group has its mask, and the masks of the chunk's earlier groups, before it
+                unsigned at = 4u * lanes_below(b, q_end / 4u) + (WINDOWED ? 4u + 4u * (lane >> 5) : 0u);
+                if (__builtin_expect(keep, 1)) *reinterpret_cast<unsigned*>(stage + at) = x;   // predicated, no branch
+                if (WINDOWED && (lane & 31) == 0 && static_cast<unsigned>(lane >> 5) < chunk_groups)
+                    *reinterpret_cast<unsigned*>(stage + at - 4u) =
+                        lane == 0 ? static_cast<unsigned>(b) : static_cast<unsigned>(b >> 32);
+                q_end += 4u * static_cast<unsigned>(__popcll(b)) + 4u * chunk_groups;
+            } else {
+                const bool keep0 = kept_first<2, RELU>(x), keep1 = kept_second<RELU>(x);
+                const unsigned long long be = __ballot(keep0), bo = __ballot(keep1);
+                unsigned at = 2u * lanes_below(bo, lanes_below(be, q_end / 2u)) +
+                              (WINDOWED ? 4u + 4u * (lane >> 4) : 0u);
+                if (WINDOWED && (lane & 15) == 0 && static_cast<unsigned>(lane >> 4) < chunk_groups) {
+                    const unsigned long long z0 = zip_bits(static_cast<unsigned>(be), static_cast<unsigned>(bo));
+                    const unsigned long long z1 = zip_bits(static_cast<unsigned>(be >> 32), static_cast<unsigned>(bo >> 32));
+                    const unsigned m = lane == 0 ? static_cast<unsigned>(z0)
+                                     : lane == 16 ? static_cast<unsigned>(z0 >> 32)
+                                     : lane == 32 ? static_cast<unsigned>(z1) : static_cast<unsigned>(z1 >> 32);
+                    *reinterpret_cast<unsigned short*>(stage + at - 4u) = static_cast<unsigned short>(m);
+                    *reinterpret_cast<unsigned short*>(stage + at - 2u) = static_cast<unsigned short>(m >> 16);
+                }
+                if (__builtin_expect(keep0, 1)) *reinterpret_cast<unsigned short*>(stage + at) = static_cast<unsigned short>(x);
+                if (__builtin_expect(keep1, 1)) *reinterpret_cast<unsigned short*>(stage + at + (keep0 ? 2u : 0u)) = static_cast<unsigned short>(x >> 16);
+                q_end += 2u * (static_cast<unsigned>(__popcll(be)) + static_cast<unsigned>(__popcll(bo))) + 4u * chunk_groups;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    // before the tile knows where its run begins: whatever fits the queue
+    int staged = 0;                               // steps staged so far, wave-uniform
+    static_for<0, G::kSteps>([&](auto hc) __attribute__((always_inline)) {
+        constexpr int h = decltype(hc)::value;
+        if (staged == h && q_end + step_bytes(h) <= static_cast<unsigned>(G::kQueueBytes)) {
+            stage_step(hc);
+            staged = h + 1;
+        }
+    });
     ZVC_TRACE_POINT(tile, 3);
+
+    // ---- 4. device-wide exclusive scan, wave 0
+    if (wave == 0) {
+        unsigned long long ex = 0;
+        if (tile != 0) {
+            const CountInputTile<W, CH, RELU, SPLIT> count_tile{a.in, a.n};
+            ex = scan_exclusive_prefix(a.counts, a.prefixes, requested, tile, lane, a.patience, a.hdr, count_tile);
+        }
+        if (lane == 0) s_prefix = ex;
+    }
+    // the tile's count has reached memory before any wave of the tile goes on (see finish_arrive)
+    if (publisher) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+    ZVC_TRACE_POINT(tile, 4);
+    const unsigned long long exclusive = uniform(s_prefix);
     unsigned wave_offset = 0, tile_total = 0;
 #pragma unroll
     for (int v = 0; v < kWaves; ++v) {
@@ -745,101 +958,42 @@ __global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(
         if (v < wave) wave_offset += t;
         tile_total += t;
     }
-
-    // ---- device-wide exclusive scan, wave 0
-    if (wave == 0) {
-        const CountInputTile<W, LOADS, ALIGNED, RELU> count_tile{a.in, a.n};
-        const unsigned long long ex = tile_exclusive_prefix(a.counts, a.prefixes, tile, tile_total,
-                                                            lane, a.patience, a.hdr, count_tile);
-        if (lane == 0) s_prefix = ex;
-        ZVC_TRACE_POINT(tile, 4);
+    if (wave == 0 && lane == 0) {
+        if (tile % kBlockTiles == kBlockTiles - 1)
+            store64(a.prefixes + tile / kBlockTiles, kPrefixValid | (exclusive + tile_total));
+        finish_arrive(a.hdr, tile);
     }
-    lds_barrier();
-    const unsigned long long exclusive = uniform(s_prefix);
-    // after the barrier, so that only this wave waits for its state stores to complete
-    if (wave == 0 && lane == 0) finish_arrive(a.hdr, tile);
 
-    // ---- compaction (section 5.2: shift non-zeros to their packed slots).
-    //      Each wave stages kStageLoads loads at a time in its own LDS slice in
-    //      packed order and writes out the lines that are complete (see
-    //      wave_flush_lines): slice byte p corresponds to global byte gline + p.
     //      A call with a buffer below the worst case (cap_values) writes a tile's
     //      run only if the run ends inside the buffer; the size is reported anyway.
     const unsigned long long tile_end_bytes =
         (exclusive + tile_total) * W +
         (WINDOWED ? 4ull * min(static_cast<size_t>(tile + 1) * G::kTileGroups, a.num_groups) : 0ull);
     if (tile_end_bytes <= a.cap_values) {
-        unsigned char* stage = s_stage[wave];
-        unsigned char* gline = nullptr;
-        unsigned pend_lo = 0, pend_end = 0;
-    #pragma unroll
-        for (int h = 0; h < G::kStageSteps; ++h) {
-            const unsigned first_rank = run[h * kStageLoads];
-            const unsigned step_total = run[(h + 1) * kStageLoads] - first_rank;
-            // windowed: the step is four windows (one per load), whose groups may end with the tensor
-            const size_t step = (static_cast<size_t>(tile) * kWaves + wave) * G::kStageSteps + h;
-            const size_t window_group0 = step * kStepGroups;
-            const unsigned valid_groups =
-                !WINDOWED || window_group0 >= a.num_groups ? 0u
-                : a.num_groups - window_group0 < kStepGroups ? static_cast<unsigned>(a.num_groups - window_group0)
-                                                             : static_cast<unsigned>(kStepGroups);
-            const unsigned step_bytes = step_total * W + 4u * valid_groups;
-            unsigned char* dst = a.values + (exclusive + wave_offset + first_rank) * W +   // wave-uniform
-                                 (WINDOWED ? 4 * (window_group0 < a.num_groups ? window_group0 : a.num_groups) : 0);
-            if (h == 0) {   // later steps continue where the previous one ended: dst == gline + pend_end
-                pend_lo = pend_end = static_cast<unsigned>(reinterpret_cast<uintptr_t>(dst) & 127u);
-                gline = dst - pend_lo;
-            }
-            const unsigned shift = pend_end;
-            if (WINDOWED && lane == 0) {
-                // the byte offset of every window that exists: its masks before it, its kept elements before it
-    #pragma unroll
-                for (int jj = 0; jj < kStageLoads; ++jj)
-                    if (static_cast<unsigned>(jj * G::kGroupsPerLoad) < valid_groups)
-                        a.offsets[step * kStageLoads + jj] =
-                            static_cast<unsigned long long>(dst - a.values) + 4u * jj * G::kGroupsPerLoad +
-                            W * (run[h * kStageLoads + jj] - first_rank);
-            }
-    #pragma unroll
-            for (int jj = 0; jj < kStageLoads; ++jj) {
-                const int j = h * kStageLoads + jj;
-                // rank of the lane's first element within the step
-                const unsigned rank0 = (run[j] - first_rank) + ((below16[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
-                const unsigned group = static_cast<unsigned>(jj * G::kGroupsPerLoad + lane / LPG);
-                unsigned char* at = stage + shift + W * (rank0 + (WINDOWED ? kMaskUnits * (group + 1u) : 0u));
-                unsigned bits = 0;
-    #pragma unroll
-                for (int c = 0; c < E; ++c) {
-                    const bool nz = element_kept<W, RELU>(cur[j], c);
-                    const unsigned v = element_of<W>(cur[j], c);
-                    bits |= (nz ? 1u : 0u) << c;
-                    if (__builtin_expect(nz, 1)) {   // predicated: write and advance in the kept lanes only
-                        if (W == 4)
-                            *reinterpret_cast<unsigned*>(at) = v;
-                        else
-                            *reinterpret_cast<unsigned short*>(at) = static_cast<unsigned short>(v);
-                        at += W;
-                    }
-                }
-                if (WINDOWED) {
-                    // the group's first lane puts the mask before the group's elements
-                    const unsigned m = group_or<LPG>(bits << field_shift);
-                    if (lane_in_group == 0 && group < valid_groups) {
-                        unsigned char* mask_at = stage + shift + W * (rank0 + kMaskUnits * group);
-                        if (W == 4) {
-                            *reinterpret_cast<unsigned*>(mask_at) = m;
-                        } else {
-                            *reinterpret_cast<unsigned short*>(mask_at) = static_cast<unsigned short>(m);
-                            *reinterpret_cast<unsigned short*>(mask_at + 2) = static_cast<unsigned short>(m >> 16);
-                        }
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+        unsigned char* const run_begin =
+            a.values + (exclusive + wave_offset) * W +
+            (WINDOWED ? 4 * (wave_group0 < a.num_groups ? wave_group0 : a.num_groups) : 0);
+        unsigned char* gzero = run_begin;
+        if (staged != 0) {
+            wave_flush<W>(gzero, stage, q_lo, q_end, staged == G::kSteps, lane);
+            zero_local = static_cast<unsigned>(gzero - run_begin);
             wave_lds_sync();
-            pend_end = shift + step_bytes;
-            wave_flush_lines<W>(gline, stage, pend_lo, pend_end, h == G::kStageSteps - 1, lane);
-            wave_lds_sync();
+        }
+        static_for<0, G::kSteps>([&](auto hc) __attribute__((always_inline)) {
+            constexpr int h = decltype(hc)::value;
+            if (h >= staged) {
+                stage_step(hc);
+                wave_lds_sync();
+                wave_flush<W>(gzero, stage, q_lo, q_end, h == G::kSteps - 1, lane);
+                zero_local = static_cast<unsigned>(gzero - run_begin);
+                wave_lds_sync();
+            }
+        });
+        if (WINDOWED && lane < CH / kWindowChunks) {
+            // the byte offset of every window that exists: its masks before it, its kept elements before it
+            const size_t window = wave_group0 / (kWindowChunks * CG) + lane;
+            if (wave_group0 + static_cast<size_t>(lane) * (kWindowChunks * CG) < a.num_groups)
+                a.offsets[window] = static_cast<unsigned long long>(run_begin - a.values) + window_local;
         }
     }
     ZVC_TRACE_POINT(tile, 5);
@@ -849,7 +1003,7 @@ __global__ __launch_bounds__(kThreads, LOADS == 8 ? 6 : 1) void compress_kernel(
         const unsigned long long total =
             4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
         *a.d_bytes = total;
-        if (WINDOWED) a.offsets[div_up(a.num_groups, G::kGroupsPerLoad)] = total;
+        if (WINDOWED) a.offsets[div_up(a.num_groups, kWindowChunks * CG)] = total;
     }
 
     if (tile == a.num_tiles - 1 && wave == 0)
@@ -1388,23 +1542,15 @@ std::atomic<unsigned> g_patience{kDefaultPatience};
 // Tile size of the encoder.  Each tile costs a fixed few nanoseconds of
 // chip-wide time (workgroup launch plus the scan's state traffic), so large
 // tensors use 64 KB tiles; smaller tensors use smaller tiles so that every CU
-// still gets several.  The limits are measured crossover points (the chip holds
-// 1024 tiles of 64 KB, 1536 of 32 KB or 2048 of 16 KB at a time; a tensor that
-// just fills one such round is served best by that size).
-#ifndef ZVC_FORCE_LOADS
-#define ZVC_FORCE_LOADS 0
-#endif
-#ifndef ZVC_FORCE_DECODER_LOADS
-#define ZVC_FORCE_DECODER_LOADS 0
-#endif
+// still gets several.  The limits are measured crossover points.
 constexpr size_t kLargeTensorBytes = size_t{56} << 20;
 constexpr size_t kMediumTensorBytes = size_t{12} << 20;
+constexpr int kMinChunks = kMinLoads * 16 * kThreads / (kWaves * kChunkBytes);   // 16 KB tiles: 16
 
-inline int choose_loads(size_t n, int w, bool aligned) {
-    if (!aligned) return kMinLoads;
-    if (ZVC_FORCE_LOADS != 0) return ZVC_FORCE_LOADS;
+inline int choose_chunks(size_t n, int w, bool split) {
+    if (split) return kMinChunks;
     const size_t bytes = n * static_cast<size_t>(w);
-    return bytes >= kLargeTensorBytes ? 16 : bytes >= kMediumTensorBytes ? 8 : 4;
+    return bytes >= kLargeTensorBytes ? 64 : bytes >= kMediumTensorBytes ? 32 : kMinChunks;
 }
 
 // The decoder's waves are independent, so its tile only sets how many staging
@@ -1412,12 +1558,12 @@ inline int choose_loads(size_t n, int w, bool aligned) {
 // at every size.
 inline int choose_decoder_loads(size_t, int, bool aligned) {
     if (!aligned) return kMinLoads;
-    return ZVC_FORCE_DECODER_LOADS != 0 ? ZVC_FORCE_DECODER_LOADS : kMinLoads;
+    return kMinLoads;
 }
 
 enum class Encoder { kPlain, kRelu, kWindowed };
 
-template <int W, int LOADS, bool ALIGNED>
+template <int W, int CH, bool SPLIT>
 void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
                         unsigned* masks, unsigned char* values, ScanState st,
                         unsigned long long* d_bytes, unsigned tiles, size_t groups,
@@ -1428,13 +1574,13 @@ void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* i
     const dim3 grid(tiles), block(kThreads);
     switch (mode) {
         case Encoder::kPlain:
-            hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, false, false>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((compress_kernel<W, CH, false, false, SPLIT>), grid, block, 0, stream, args);
             break;
         case Encoder::kRelu:
-            hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, true, false>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((compress_kernel<W, CH, true, false, SPLIT>), grid, block, 0, stream, args);
             break;
         case Encoder::kWindowed:
-            hipLaunchKernelGGL((compress_kernel<W, LOADS, ALIGNED, false, true>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((compress_kernel<W, CH, false, true, SPLIT>), grid, block, 0, stream, args);
             break;
     }
 }
@@ -1457,22 +1603,21 @@ void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                        interleave);
 }
 
-// Picks the instantiation for (w, loads, aligned).  Unaligned tensors always
-// use the smallest tile.
+// Picks the instantiation for (w, chunks per wave).  16-bit elements at an odd
+// half dword always use the smallest tile.
 template <typename... Args>
-void launch_compress(int w, int loads, bool aligned, Args... args) {
-    if (!aligned) {
-        if (w == 4) launch_compress_as<4, kMinLoads, false>(args...);
-        else launch_compress_as<2, kMinLoads, false>(args...);
-    } else if (loads == 16) {
-        if (w == 4) launch_compress_as<4, 16, true>(args...);
-        else launch_compress_as<2, 16, true>(args...);
-    } else if (loads == 8) {
-        if (w == 4) launch_compress_as<4, 8, true>(args...);
-        else launch_compress_as<2, 8, true>(args...);
+void launch_compress(int w, int chunks, bool split, Args... args) {
+    if (split) {
+        launch_compress_as<2, kMinChunks, true>(args...);
+    } else if (chunks == 64) {
+        if (w == 4) launch_compress_as<4, 64, false>(args...);
+        else launch_compress_as<2, 64, false>(args...);
+    } else if (chunks == 32) {
+        if (w == 4) launch_compress_as<4, 32, false>(args...);
+        else launch_compress_as<2, 32, false>(args...);
     } else {
-        if (w == 4) launch_compress_as<4, 4, true>(args...);
-        else launch_compress_as<2, 4, true>(args...);
+        if (w == 4) launch_compress_as<4, kMinChunks, false>(args...);
+        else launch_compress_as<2, kMinChunks, false>(args...);
     }
 }
 
@@ -1516,16 +1661,16 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
                                reinterpret_cast<unsigned long long*>(d_offsets), 0ull);
         return hip_ok(hipGetLastError());
     }
-    const bool al = aligned_to(d_in, 16);
-    const int loads = choose_loads(n, w, al);
-    const size_t tiles = tiles_for(n, w, loads);
+    const bool split = !aligned_to(d_in, 4);        // 16-bit elements at an odd half dword
+    const int chunks = choose_chunks(n, w, split);
+    const size_t tiles = div_up(n * static_cast<size_t>(w), static_cast<size_t>(kWaves) * chunks * kChunkBytes);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     // the scan state is zero between calls: the kernel cleans up after itself
     const size_t groups = div_up(n, 32);
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
     unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    launch_compress(w, loads, al, mode, stream, in, n, masks,
+    launch_compress(w, chunks, split, mode, stream, in, n, masks,
                     mode == Encoder::kWindowed ? static_cast<unsigned char*>(d_out) : values,
                     scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups,
                     !bounded ? ~0ull : out_cap - (mode == Encoder::kWindowed ? 0 : 4 * groups),
