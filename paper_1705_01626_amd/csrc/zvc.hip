@@ -50,8 +50,11 @@ constexpr int kFinishLanes = 64;              // arrival counters, one 128-byte 
 constexpr size_t kHeaderBytes = 256 + 128 * (kFinishLanes + 1);  // header, then the scan state
 constexpr int kMinLoads = 4;                  // smallest tile: 16 KB (sizes the workspace)
 constexpr int kStageLoads = 4;                // 16-byte loads a wave stages through LDS at a time
-constexpr int kBlockTiles = 64;               // one running prefix is published per 64 tiles
-constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
+constexpr int kBlockTiles = 256;              // one running prefix is published per 256 tiles
+#ifndef ZVC_POLL_SLEEP
+#define ZVC_POLL_SLEEP 8
+#endif
+constexpr int kPollSleep = ZVC_POLL_SLEEP;  //               // s_sleep units (64 clocks each) between polls
 
 // A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
 template <int W, int LOADS>
@@ -80,7 +83,10 @@ struct Geometry {
 // ones on this memory system (each wave instruction still covers whole
 // 128-byte lines).
 constexpr int kChunkBytes = 4 * kWaveSize;
-constexpr int kStepChunks = 16;               // chunks a wave stages between two flushes: 4 KB of input
+#ifndef ZVC_STEP_CHUNKS
+#define ZVC_STEP_CHUNKS 16
+#endif
+constexpr int kStepChunks = ZVC_STEP_CHUNKS;  // chunks a wave stages between two flushes: 2 KB of input
 template <int W, int CH>
 struct EncoderGeometry {
     static constexpr int kChunkElems = kChunkBytes / W;          // 64 | 128
@@ -95,11 +101,16 @@ struct EncoderGeometry {
     static constexpr int kStepGroups = kStepChunks * kChunkGroups;
     // the most a step can add to the wave's queue (windowed stream: its masks too)
     static constexpr int kStepMaxBytes = kStepChunks * kChunkBytes + 4 * kStepGroups;
-    // A wave's LDS queue: room for half the wave's input (what a wave of a tensor
-    // that is at most half non-zero can stage before its tile knows where its run
-    // begins), never less than a carried-over partial line plus one step.
-    static constexpr int kQueueBytes =
-        (CH * kChunkBytes / 2 > kStepMaxBytes ? CH * kChunkBytes / 2 : kStepMaxBytes) + 256;
+    // A wave's LDS queue.  What is in it when the tile learns where its run
+    // begins has cost the tile no time; what does not fit waits for that moment.
+    // The largest tile's queue holds half a wave's input less a little, so that
+    // five workgroups share a CU's LDS; the smaller tiles' queues hold a step
+    // more than half.  Never less than a carried-over partial line plus a step.
+#ifndef ZVC_QUEUE64
+#define ZVC_QUEUE64 8704
+#endif
+    static constexpr int kQueueBytes = CH == 64 ? ZVC_QUEUE64 : CH * kChunkBytes / 2 + kStepMaxBytes + 256;
+    static_assert(kQueueBytes >= 128 + kStepMaxBytes, "a step always fits behind a carried-over partial line");
     static_assert(CH % kStepChunks == 0, "a wave's chunks are staged in whole steps");
     static_assert(kTileElems < (1 << 24), "tile totals fit the arrival word");
 };
@@ -130,8 +141,8 @@ static_assert(sizeof(WsHeader) == kHeaderBytes, "header size");
 // Scan state in the workspace, after the header:
 //   counts[t]   : 32-bit word per tile, top bit = published, rest = the tile's
 //                 own count of kept elements;
-//   prefixes[b] : 64-bit word per block of 64 tiles, top bit = published, rest
-//                 = kept elements in all tiles up to and including tile 64b+63.
+//   prefixes[b] : 64-bit word per block of kBlockTiles tiles, top bit = published,
+//                 rest = kept elements in all tiles up to and including the block's last.
 constexpr unsigned kCountValid = 0x80000000u;
 constexpr unsigned long long kPrefixValid = 1ull << 63;
 
@@ -198,6 +209,29 @@ __device__ inline unsigned uniform(unsigned v) {
 __device__ inline unsigned long long uniform(unsigned long long v) {
     return (static_cast<unsigned long long>(uniform(static_cast<unsigned>(v >> 32))) << 32) |
            uniform(static_cast<unsigned>(v));
+}
+
+// Lane `src` (wave-uniform) of v.
+__device__ inline unsigned lane_value(unsigned v, int src) {
+    return static_cast<unsigned>(__builtin_amdgcn_readlane(static_cast<int>(v), src));
+}
+__device__ inline unsigned long long lane_value(unsigned long long v, int src) {
+    return (static_cast<unsigned long long>(lane_value(static_cast<unsigned>(v >> 32), src)) << 32) |
+           lane_value(static_cast<unsigned>(v), src);
+}
+
+// Sum over the wave of one value per lane (each below 2^26), wave-uniform
+// result.  DPP adds within each row of 16 lanes (pairs, quads, half-row mirror,
+// row mirror), then the four row sums are read out and added on the scalar
+// unit: a dozen instructions and no lane-index registers, which matters where
+// the caller holds a tile's data in registers and every cycle of the scan is
+// waited for by the tile's other waves.
+__device__ inline unsigned wave_sum_small(unsigned v) {
+    v += static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0xB1, 0xF, 0xF, true));
+    v += static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x4E, 0xF, 0xF, true));
+    v += static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x141, 0xF, 0xF, true));
+    v += static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), 0x140, 0xF, 0xF, true));
+    return lane_value(v, 0) + lane_value(v, 16) + lane_value(v, 32) + lane_value(v, 48);
 }
 
 // OR over each aligned group of LANES lanes (8 or 4), result in every lane of
@@ -435,8 +469,8 @@ __device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetch
 // "offset to the next mask", section 5.1, for a whole tile at a time).
 //
 // Protocol.  Every tile publishes its own count (the wave of the tile that
-// finishes its zero tests last does).  Tile 64b+63 also publishes the running
-// total up to and including itself (one prefix per block of 64 tiles).  A tile
+// finishes its zero tests last does).  The last tile of every block of 256 also
+// publishes the running total up to and including itself.  A tile
 // finds the nearest published block prefix behind it and adds the counts of the
 // tiles between that block and itself, two counts per 8-byte load across the
 // wave.  In steady state that is a few hundred counts and the walk takes one
@@ -458,23 +492,14 @@ __device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetch
 // (`count_tile`, a re-read of that tile's input) and publishes it, so the walk
 // ends whatever the dispatch order.
 //
-// The walk is split in two so that its first memory round trip costs the tile
-// nothing: scan_request_prefixes() is called when the tile starts (the prefix
-// found then is a few blocks further back than one found later would be: a few
-// more counts to add), scan_exclusive_prefix() when the tile's own zero tests
-// are done.  Both are called by one whole wave of the tile.
-__device__ inline unsigned long long scan_request_prefixes(const unsigned long long* prefixes,
-                                                           unsigned tile, int lane) {
-    const int idx = static_cast<int>(tile) / kBlockTiles - 1 - lane;
-    return idx >= 0 ? load64(prefixes + idx) : kPrefixValid;   // before block 0 the prefix is 0
-}
-
-// Returns the number of kept elements in all tiles before `tile` (not 0);
-// `requested` is what scan_request_prefixes() returned to this lane.
+// Called by one whole wave of the tile, when the tile's own zero tests are done
+// (asking for the prefixes earlier, while the tile's loads are under way, saves
+// a round trip but finds a prefix further back, and the extra counts to read
+// cost more than the round trip).  Returns the number of kept elements in all
+// tiles before `tile` (not 0).
 template <class CountTile>
 __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
                                                            const unsigned long long* prefixes,
-                                                           unsigned long long requested,
                                                            unsigned tile, int lane,
                                                            unsigned patience, WsHeader* hdr,
                                                            const CountTile& count_tile) {
@@ -483,18 +508,17 @@ __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
     int bb = t / kBlockTiles - 1;
     unsigned long long base = 0;
     int lo = 0;
-    unsigned long long pv = requested;
     while (true) {
+        const int idx = bb - lane;
+        const unsigned long long pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;   // before block 0 the prefix is 0
         const unsigned long long have = __ballot((pv & kPrefixValid) != 0);
         if (have) {
             const int k = __ffsll(static_cast<long long>(have)) - 1;
-            base = __shfl(pv, k) & ~kPrefixValid;
+            base = lane_value(pv, k) & ~kPrefixValid;
             lo = (bb - k + 1) * kBlockTiles;   // first tile after that block
             break;
         }
         bb -= kWaveSize;
-        const int idx = bb - lane;
-        pv = idx >= 0 ? load64(prefixes + idx) : kPrefixValid;
     }
     // Counts of tiles lo .. t-1, a pair per 8-byte load (lo is a multiple of 64:
     // pairs are aligned).  A lane adds up its pairs in order as far as they are
@@ -520,7 +544,9 @@ __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
             }
         }
         const unsigned long long holes = __ballot(hole >= 0);
-        if (!holes) return base + wave_sum(static_cast<unsigned long long>(sum));
+        if (!holes)   // (halves, so that no partial sum can overflow whatever the distance walked)
+            return base + wave_sum_small(sum & 0xFFFFu) +
+                   (static_cast<unsigned long long>(wave_sum_small(sum >> 16)) << 16);
         if (polls < patience) {
             ++polls;
             __builtin_amdgcn_s_sleep(kPollSleep);
@@ -528,7 +554,7 @@ __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
         }
         // help one unpublished predecessor, then look again without waiting anew
         const int hole_lane = __ffsll(static_cast<long long>(holes)) - 1;
-        const int q = __shfl(hole, hole_lane);
+        const int q = static_cast<int>(lane_value(static_cast<unsigned>(hole), hole_lane));
         const unsigned helped_count = count_tile(static_cast<unsigned>(q), lane);
         unsigned old = 0;
         if (lane == 0) {
@@ -666,14 +692,14 @@ struct CountInputTile {
         const size_t last = (n * W - 1) / 4;
         const unsigned room = last - d0 < kTileDwords ? static_cast<unsigned>(last - d0) : kTileDwords;
         const bool half_tail = W == 2 && (n & 1u) != 0u && room < kTileDwords;
-        unsigned long long count = 0;
+        unsigned count = 0;
 #pragma unroll 1
         for (unsigned i = 0; i < kTileDwords; i += kWaveSize) {
             const unsigned x = load_dword_ragged<SPLIT>(in + d0 * 4, i + lane, room, half_tail);
             count += kept_first<W, RELU>(x) ? 1u : 0u;
             if (W == 2) count += kept_second<RELU>(x) ? 1u : 0u;
         }
-        return static_cast<unsigned>(wave_sum(count));
+        return wave_sum_small(count);      // a lane counts at most 512 elements
     }
 };
 
@@ -746,7 +772,7 @@ template <int W, int CH, bool RELU, bool WINDOWED, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     using G = EncoderGeometry<W, CH>;
     constexpr int CG = G::kChunkGroups;
-    constexpr int kAhead = CH < 32 ? CH : 32;     // loads a wave keeps in flight: 8 KB
+    constexpr int kAhead = CH;                    // all of a wave's loads are in flight from the start (measured: 3-6 % over 8 KB at a time)
     constexpr int kWindowChunks = 4;              // a window of the windowed stream: 1 KB of input
     static_assert(W == 2 || !SPLIT, "only 16-bit elements can sit at an odd half dword");
 
@@ -762,15 +788,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     ZVC_TRACE_POINT(tile, 0);
     if (tid == 0) s_arrive = 0u;
 
-    // the scan's first round trip starts now and is looked at after the zero tests
-    unsigned long long requested = 0;
-    if (wave == 0 && tile != 0) requested = scan_request_prefixes(a.prefixes, tile, lane);
-
     const size_t wave_elem0 = static_cast<size_t>(tile) * G::kTileElems + static_cast<size_t>(wave) * G::kWaveElems;
     const size_t wave_group0 = static_cast<size_t>(tile) * G::kTileGroups + static_cast<size_t>(wave) * G::kWaveGroups;
     const size_t wave_dword0 = wave_elem0 / (4 / W);
 
-    // ---- 1. loads, zero tests, masks (section 5.2: words compared to zero form the mask bits)
+    // ---- 1. loads, zero tests, masks (section 5.2: words compared to zero form the mask
+    //         bits) and, fused with them where the queue has room, 3. compaction (section
+    //         5.2: shift non-zeros to their packed slots)
     unsigned cur[CH];
     unsigned mask_reg[G::kMaskRegs];
     unsigned step_total[G::kSteps];               // wave-uniform
@@ -778,37 +802,94 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     for (int r = 0; r < G::kMaskRegs; ++r) mask_reg[r] = 0u;
 #pragma unroll
     for (int h = 0; h < G::kSteps; ++h) step_total[h] = 0u;
-
-    const auto zero_test = [&](auto kc) __attribute__((always_inline)) {
-        constexpr int k = decltype(kc)::value;
-        const unsigned x = cur[k];
-        if constexpr (W == 4) {
-            const unsigned long long b = __ballot(kept_first<4, RELU>(x));
-            step_total[k / kStepChunks] += static_cast<unsigned>(__popcll(b));
-            if (!WINDOWED) {
-                set_lane<(2 * k) % kWaveSize>(mask_reg[(2 * k) / kWaveSize], static_cast<unsigned>(b));
-                set_lane<(2 * k + 1) % kWaveSize>(mask_reg[(2 * k + 1) / kWaveSize], static_cast<unsigned>(b >> 32));
-            }
-        } else {
-            const unsigned long long be = __ballot(kept_first<2, RELU>(x));
-            const unsigned long long bo = __ballot(kept_second<RELU>(x));
-            step_total[k / kStepChunks] += static_cast<unsigned>(__popcll(be)) + static_cast<unsigned>(__popcll(bo));
-            if (!WINDOWED) {
-                const unsigned long long z0 = zip_bits(static_cast<unsigned>(be), static_cast<unsigned>(bo));
-                const unsigned long long z1 = zip_bits(static_cast<unsigned>(be >> 32), static_cast<unsigned>(bo >> 32));
-                set_lane<(4 * k) % kWaveSize>(mask_reg[(4 * k) / kWaveSize], static_cast<unsigned>(z0));
-                set_lane<(4 * k + 1) % kWaveSize>(mask_reg[(4 * k + 1) / kWaveSize], static_cast<unsigned>(z0 >> 32));
-                set_lane<(4 * k + 2) % kWaveSize>(mask_reg[(4 * k + 2) / kWaveSize], static_cast<unsigned>(z1));
-                set_lane<(4 * k + 3) % kWaveSize>(mask_reg[(4 * k + 3) / kWaveSize], static_cast<unsigned>(z1 >> 32));
-            }
-        }
-        if (k == 0) ZVC_TRACE_POINT(tile, 1);
+    unsigned char* stage = s_stage[wave];
+    unsigned q_lo = 0, q_end = 0;                 // the wave's queue: slice offsets, wave-uniform
+    unsigned zero_local = 0;                      // offset within the wave's run of slice offset 0
+    unsigned window_local = 0;                    // lane i: offset within the wave's run of its window i
+    // groups of the tensor among `count` groups of this wave from `first_group` on (fewer where the tensor ends)
+    const auto groups_from = [&](int first_group, int count) -> unsigned {
+        const size_t g = wave_group0 + static_cast<size_t>(first_group);
+        return g >= a.num_groups ? 0u
+             : a.num_groups - g < static_cast<size_t>(count) ? static_cast<unsigned>(a.num_groups - g)
+                                                             : static_cast<unsigned>(count);
     };
 
+    // One chunk.  TEST: its masks and its share of the totals.  STAGE: its kept
+    // elements into the queue at q_end.  Both use the same ballots.
+    const auto chunk = [&](auto kc, auto test_c, auto stage_c) __attribute__((always_inline)) {
+        constexpr int k = decltype(kc)::value;
+        constexpr bool TEST = decltype(test_c)::value, STAGE = decltype(stage_c)::value;
+        const unsigned x = cur[k];
+        const unsigned chunk_groups = STAGE && WINDOWED ? groups_from(k * CG, CG) : 0u;
+        if (STAGE && WINDOWED && k % kWindowChunks == 0)
+            set_lane<k / kWindowChunks>(window_local, zero_local + q_end);
+        if constexpr (W == 4) {
+            const bool keep = kept_first<4, RELU>(x);
+            const unsigned long long b = __ballot(keep);
+            const unsigned kept = static_cast<unsigned>(__popcll(b));
+            if (TEST) {
+                step_total[k / kStepChunks] += kept;
+                if (!WINDOWED) {
+                    set_lane<(2 * k) % kWaveSize>(mask_reg[(2 * k) / kWaveSize], static_cast<unsigned>(b));
+                    set_lane<(2 * k + 1) % kWaveSize>(mask_reg[(2 * k + 1) / kWaveSize], static_cast<unsigned>(b >> 32));
+                }
+            }
+            if (STAGE) {
+                // windowed: the lane's group has its mask, and the masks of the chunk's earlier groups, before it
+                const unsigned at = 4u * lanes_below(b, 0u) + q_end + (WINDOWED ? 4u + 4u * (lane >> 5) : 0u);
+                if (__builtin_expect(keep, 1)) *reinterpret_cast<unsigned*>(stage + at) = x;   // predicated, no branch
+                if (WINDOWED && (lane & 31) == 0 && static_cast<unsigned>(lane >> 5) < chunk_groups)
+                    *reinterpret_cast<unsigned*>(stage + at - 4u) =
+                        lane == 0 ? static_cast<unsigned>(b) : static_cast<unsigned>(b >> 32);
+                q_end += 4u * kept + 4u * chunk_groups;
+            }
+        } else {
+            const bool keep0 = kept_first<2, RELU>(x), keep1 = kept_second<RELU>(x);
+            const unsigned long long be = __ballot(keep0), bo = __ballot(keep1);
+            const unsigned kept = static_cast<unsigned>(__popcll(be)) + static_cast<unsigned>(__popcll(bo));
+            unsigned long long z0 = 0, z1 = 0;
+            if ((TEST && !WINDOWED) || (STAGE && WINDOWED)) {
+                z0 = zip_bits(static_cast<unsigned>(be), static_cast<unsigned>(bo));
+                z1 = zip_bits(static_cast<unsigned>(be >> 32), static_cast<unsigned>(bo >> 32));
+            }
+            if (TEST) {
+                step_total[k / kStepChunks] += kept;
+                if (!WINDOWED) {
+                    set_lane<(4 * k) % kWaveSize>(mask_reg[(4 * k) / kWaveSize], static_cast<unsigned>(z0));
+                    set_lane<(4 * k + 1) % kWaveSize>(mask_reg[(4 * k + 1) / kWaveSize], static_cast<unsigned>(z0 >> 32));
+                    set_lane<(4 * k + 2) % kWaveSize>(mask_reg[(4 * k + 2) / kWaveSize], static_cast<unsigned>(z1));
+                    set_lane<(4 * k + 3) % kWaveSize>(mask_reg[(4 * k + 3) / kWaveSize], static_cast<unsigned>(z1 >> 32));
+                }
+            }
+            if (STAGE) {
+                const unsigned at = 2u * lanes_below(bo, lanes_below(be, 0u)) + q_end +
+                                    (WINDOWED ? 4u + 4u * (lane >> 4) : 0u);
+                if (WINDOWED && (lane & 15) == 0 && static_cast<unsigned>(lane >> 4) < chunk_groups) {
+                    const unsigned m = lane == 0 ? static_cast<unsigned>(z0)
+                                     : lane == 16 ? static_cast<unsigned>(z0 >> 32)
+                                     : lane == 32 ? static_cast<unsigned>(z1) : static_cast<unsigned>(z1 >> 32);
+                    *reinterpret_cast<unsigned short*>(stage + at - 4u) = static_cast<unsigned short>(m);
+                    *reinterpret_cast<unsigned short*>(stage + at - 2u) = static_cast<unsigned short>(m >> 16);
+                }
+                if (__builtin_expect(keep0, 1)) *reinterpret_cast<unsigned short*>(stage + at) = static_cast<unsigned short>(x);
+                if (__builtin_expect(keep1, 1)) *reinterpret_cast<unsigned short*>(stage + at + (keep0 ? 2u : 0u)) = static_cast<unsigned short>(x >> 16);
+                q_end += 2u * kept + 4u * chunk_groups;
+            }
+        }
+        if (TEST && k == 0) ZVC_TRACE_POINT(tile, 1);
+    };
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+
     // A wave that lies wholly inside the tensor needs no bounds checks: it keeps
-    // kAhead loads in flight and tests each chunk as it arrives.  The barrier makes
-    // the cleared arrival word visible to the tile's waves; it comes after the
-    // first loads have been issued, so it costs them nothing.
+    // kAhead loads in flight and tests each chunk as it arrives.  A step is
+    // compacted in the same pass while the queue is sure to hold it whatever its
+    // density (the first two steps always are): the compaction then happens
+    // while the wave would otherwise wait for its loads, and needs nothing from
+    // other tiles.  The barrier makes the cleared arrival word visible to the
+    // tile's waves; it comes after the first loads have been issued, so it costs
+    // them nothing.
+    int staged = 0;                               // steps in the queue so far, wave-uniform
     if (wave_elem0 + G::kWaveElems <= a.n) {
         static_for<0, kAhead>([&](auto kc) __attribute__((always_inline)) {
             constexpr int k = decltype(kc)::value;
@@ -816,13 +897,28 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
             __builtin_amdgcn_sched_barrier(0);   // in the order in which the tests use them
         });
         lds_barrier();
-        static_for<0, CH>([&](auto kc) __attribute__((always_inline)) {
-            constexpr int k = decltype(kc)::value;
-            zero_test(kc);
-            if constexpr (k + kAhead < CH)
-                cur[k + kAhead] =
-                    load_dword<SPLIT>(a.in, wave_dword0 + static_cast<size_t>(k + kAhead) * kWaveSize + lane);
-            __builtin_amdgcn_sched_barrier(0);
+        static_for<0, G::kSteps>([&](auto hc) __attribute__((always_inline)) {
+            constexpr int h = decltype(hc)::value;
+            const bool fuse = staged == h && q_end + G::kStepMaxBytes <= static_cast<unsigned>(G::kQueueBytes);
+            const auto next_load = [&](auto kc) __attribute__((always_inline)) {
+                constexpr int k = decltype(kc)::value;
+                if constexpr (k + kAhead < CH)
+                    cur[k + kAhead] =
+                        load_dword<SPLIT>(a.in, wave_dword0 + static_cast<size_t>(k + kAhead) * kWaveSize + lane);
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            if (fuse) {
+                static_for<h * kStepChunks, (h + 1) * kStepChunks>([&](auto kc) __attribute__((always_inline)) {
+                    chunk(kc, yes, yes);
+                    next_load(kc);
+                });
+                staged = h + 1;
+            } else {
+                static_for<h * kStepChunks, (h + 1) * kStepChunks>([&](auto kc) __attribute__((always_inline)) {
+                    chunk(kc, yes, no);
+                    next_load(kc);
+                });
+            }
         });
     } else if (wave_elem0 < a.n) {
         // the wave that holds the tensor's end
@@ -833,11 +929,12 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         static_for<0, CH>([&](auto kc) __attribute__((always_inline)) {
             constexpr int k = decltype(kc)::value;
             cur[k] = load_dword_ragged<SPLIT>(base, static_cast<unsigned>(k * kWaveSize + lane), room, half_tail);
+            asm volatile("" : "+v"(cur[k]));     // (or the compiler keeps the masked halves of all chunks for the tests)
             __builtin_amdgcn_sched_barrier(0);
         });
         lds_barrier();
         static_for<0, CH>([&](auto kc) __attribute__((always_inline)) {
-            zero_test(kc);
+            chunk(kc, yes, no);
             __builtin_amdgcn_sched_barrier(0);
         });
     } else {
@@ -872,62 +969,18 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         }
     }
 
-    // ---- 3./5. compaction (section 5.2: shift non-zeros to their packed slots)
-    unsigned char* stage = s_stage[wave];
-    unsigned q_lo = 0, q_end = 0;                 // the wave's queue: slice offsets, wave-uniform
-    unsigned zero_local = 0;                      // offset within the wave's run of slice offset 0
-    unsigned window_local = 0;                    // lane i: offset within the wave's run of its window i
-    // groups of the tensor in chunk k of this wave: CG, fewer where the tensor ends
-    const auto groups_from = [&](int first_group, int count) -> unsigned {
-        const size_t g = wave_group0 + static_cast<size_t>(first_group);
-        return g >= a.num_groups ? 0u
-             : a.num_groups - g < static_cast<size_t>(count) ? static_cast<unsigned>(a.num_groups - g)
-                                                             : static_cast<unsigned>(count);
-    };
+    // ---- 3. more of the compaction before the tile knows where its run begins: the steps
+    //         that were not sure to fit but, now that their size is known, do
     const auto step_bytes = [&](int h) -> unsigned {
         return step_total[h] * W + (WINDOWED ? 4u * groups_from(h * G::kStepGroups, G::kStepGroups) : 0u);
     };
     const auto stage_step = [&](auto hc) __attribute__((always_inline)) {
         constexpr int h = decltype(hc)::value;
-        static_for<0, kStepChunks>([&](auto jc) __attribute__((always_inline)) {
-            constexpr int k = h * kStepChunks + decltype(jc)::value;
-            const unsigned x = cur[k];
-            const unsigned chunk_groups = WINDOWED ? groups_from(k * CG, CG) : 0u;
-            if (WINDOWED && k % kWindowChunks == 0)
-                set_lane<k / kWindowChunks>(window_local, zero_local + q_end);
-            if constexpr (W == 4) {
-                const bool keep = kept_first<4, RELU>(x);
-                const unsigned long long b = __ballot(keep);
-                // windowed: the lane's group has its mask, and the masks of the chunk's earlier groups, before it
-                unsigned at = 4u * lanes_below(b, q_end / 4u) + (WINDOWED ? 4u + 4u * (lane >> 5) : 0u);
-                if (__builtin_expect(keep, 1)) *reinterpret_cast<unsigned*>(stage + at) = x;   // predicated, no branch
-                if (WINDOWED && (lane & 31) == 0 && static_cast<unsigned>(lane >> 5) < chunk_groups)
-                    *reinterpret_cast<unsigned*>(stage + at - 4u) =
-                        lane == 0 ? static_cast<unsigned>(b) : static_cast<unsigned>(b >> 32);
-                q_end += 4u * static_cast<unsigned>(__popcll(b)) + 4u * chunk_groups;
-            } else {
-                const bool keep0 = kept_first<2, RELU>(x), keep1 = kept_second<RELU>(x);
-                const unsigned long long be = __ballot(keep0), bo = __ballot(keep1);
-                unsigned at = 2u * lanes_below(bo, lanes_below(be, q_end / 2u)) +
-                              (WINDOWED ? 4u + 4u * (lane >> 4) : 0u);
-                if (WINDOWED && (lane & 15) == 0 && static_cast<unsigned>(lane >> 4) < chunk_groups) {
-                    const unsigned long long z0 = zip_bits(static_cast<unsigned>(be), static_cast<unsigned>(bo));
-                    const unsigned long long z1 = zip_bits(static_cast<unsigned>(be >> 32), static_cast<unsigned>(bo >> 32));
-                    const unsigned m = lane == 0 ? static_cast<unsigned>(z0)
-                                     : lane == 16 ? static_cast<unsigned>(z0 >> 32)
-                                     : lane == 32 ? static_cast<unsigned>(z1) : static_cast<unsigned>(z1 >> 32);
-                    *reinterpret_cast<unsigned short*>(stage + at - 4u) = static_cast<unsigned short>(m);
-                    *reinterpret_cast<unsigned short*>(stage + at - 2u) = static_cast<unsigned short>(m >> 16);
-                }
-                if (__builtin_expect(keep0, 1)) *reinterpret_cast<unsigned short*>(stage + at) = static_cast<unsigned short>(x);
-                if (__builtin_expect(keep1, 1)) *reinterpret_cast<unsigned short*>(stage + at + (keep0 ? 2u : 0u)) = static_cast<unsigned short>(x >> 16);
-                q_end += 2u * (static_cast<unsigned>(__popcll(be)) + static_cast<unsigned>(__popcll(bo))) + 4u * chunk_groups;
-            }
+        static_for<h * kStepChunks, (h + 1) * kStepChunks>([&](auto kc) __attribute__((always_inline)) {
+            chunk(kc, no, yes);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
-    // before the tile knows where its run begins: whatever fits the queue
-    int staged = 0;                               // steps staged so far, wave-uniform
     static_for<0, G::kSteps>([&](auto hc) __attribute__((always_inline)) {
         constexpr int h = decltype(hc)::value;
         if (staged == h && q_end + step_bytes(h) <= static_cast<unsigned>(G::kQueueBytes)) {
@@ -940,11 +993,17 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     // ---- 4. device-wide exclusive scan, wave 0
     if (wave == 0) {
         unsigned long long ex = 0;
+#ifdef ZVC_SCAN_PRIO
+        __builtin_amdgcn_s_setprio(3);
+#endif
         if (tile != 0) {
             const CountInputTile<W, CH, RELU, SPLIT> count_tile{a.in, a.n};
-            ex = scan_exclusive_prefix(a.counts, a.prefixes, requested, tile, lane, a.patience, a.hdr, count_tile);
+            ex = scan_exclusive_prefix(a.counts, a.prefixes, tile, lane, a.patience, a.hdr, count_tile);
         }
         if (lane == 0) s_prefix = ex;
+#ifdef ZVC_SCAN_PRIO
+        __builtin_amdgcn_s_setprio(0);
+#endif
     }
     // the tile's count has reached memory before any wave of the tile goes on (see finish_arrive)
     if (publisher) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
