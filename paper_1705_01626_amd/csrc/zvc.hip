@@ -51,10 +51,7 @@ constexpr size_t kHeaderBytes = 256 + 128 * (kFinishLanes + 1);  // header, then
 constexpr int kMinLoads = 4;                  // smallest tile: 16 KB (sizes the workspace)
 constexpr int kStageLoads = 4;                // 16-byte loads a wave stages through LDS at a time
 constexpr int kBlockTiles = 256;              // one running prefix is published per 256 tiles
-#ifndef ZVC_POLL_SLEEP
-#define ZVC_POLL_SLEEP 8
-#endif
-constexpr int kPollSleep = ZVC_POLL_SLEEP;  //               // s_sleep units (64 clocks each) between polls
+constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
 
 // A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
 template <int W, int LOADS>
@@ -76,26 +73,23 @@ struct Geometry {
 
 // The encoder's tile.  A wave reads its part of the tensor one dword per lane
 // (a chunk: 256 bytes, 64 fp32 or 128 16-bit elements, 2 or 4 masks), CH chunks
-// per wave, four waves per tile: 16, 32 or 64 KB for CH = 16, 32, 64.  With one
+// per wave, WV waves per tile (the workgroup): WV x CH / 4 KB.  With one
 // element (or one pair) per lane a ballot of the zero test is two masks as they
 // stand and its mbcnt is the packed position, so a chunk costs a handful of
 // vector instructions.  Streaming 4-byte accesses measure as fast as 16-byte
 // ones on this memory system (each wave instruction still covers whole
 // 128-byte lines).
 constexpr int kChunkBytes = 4 * kWaveSize;
-#ifndef ZVC_STEP_CHUNKS
-#define ZVC_STEP_CHUNKS 16
-#endif
-constexpr int kStepChunks = ZVC_STEP_CHUNKS;  // chunks a wave stages between two flushes: 2 KB of input
-template <int W, int CH>
+constexpr int kStepChunks = 8;                // chunks a wave stages between two flushes: 2 KB of input
+template <int W, int CH, int WV>
 struct EncoderGeometry {
     static constexpr int kChunkElems = kChunkBytes / W;          // 64 | 128
     static constexpr int kChunkGroups = kChunkElems / 32;        // masks per chunk: 2 | 4
     static constexpr int kWaveElems = CH * kChunkElems;
     static constexpr int kWaveGroups = CH * kChunkGroups;
-    static constexpr int kTileBytes = kWaves * CH * kChunkBytes;
-    static constexpr int kTileElems = kWaves * kWaveElems;
-    static constexpr int kTileGroups = kWaves * kWaveGroups;
+    static constexpr int kTileBytes = WV * CH * kChunkBytes;
+    static constexpr int kTileElems = WV * kWaveElems;
+    static constexpr int kTileGroups = WV * kWaveGroups;
     static constexpr int kSteps = CH / kStepChunks;
     static constexpr int kMaskRegs = (kWaveGroups + kWaveSize - 1) / kWaveSize;
     static constexpr int kStepGroups = kStepChunks * kChunkGroups;
@@ -103,13 +97,12 @@ struct EncoderGeometry {
     static constexpr int kStepMaxBytes = kStepChunks * kChunkBytes + 4 * kStepGroups;
     // A wave's LDS queue.  What is in it when the tile learns where its run
     // begins has cost the tile no time; what does not fit waits for that moment.
-    // The largest tile's queue holds half a wave's input less a little, so that
-    // five workgroups share a CU's LDS; the smaller tiles' queues hold a step
-    // more than half.  Never less than a carried-over partial line plus a step.
-#ifndef ZVC_QUEUE64
-#define ZVC_QUEUE64 8704
-#endif
-    static constexpr int kQueueBytes = CH == 64 ? ZVC_QUEUE64 : CH * kChunkBytes / 2 + kStepMaxBytes + 256;
+    // Room for half the wave's input (a tensor that is at most half non-zero is
+    // staged whole before the scan ends) plus a little, never less than a
+    // carried-over partial line plus a step.  (More workgroups per CU with a
+    // smaller queue measure the same or worse.)
+    static constexpr int kQueueBytes =
+        CH == 64 ? 8704 : (CH * kChunkBytes / 2 > kStepMaxBytes ? CH * kChunkBytes / 2 : kStepMaxBytes) + 256;
     static_assert(kQueueBytes >= 128 + kStepMaxBytes, "a step always fits behind a carried-over partial line");
     static_assert(CH % kStepChunks == 0, "a wave's chunks are staged in whole steps");
     static_assert(kTileElems < (1 << 24), "tile totals fit the arrival word");
@@ -165,20 +158,6 @@ inline size_t decoder_area_bytes(size_t chunks) {   // chunk_prefix, chunk_total
 }
 
 // ------------------------------------------------------------ device helpers
-// Developer instrumentation, compiled in with -DZVC_TRACE only: lane 0 of a
-// tile's first wave stamps the device-wide 100 MHz clock at a few points into a
-// caller-provided buffer of 8 words per tile (zvc_trace_set).
-#ifdef ZVC_TRACE
-__device__ unsigned long long* g_trace_words;
-#define ZVC_TRACE_POINT(tile, k)                                                          \
-    do {                                                                                  \
-        if (threadIdx.x == 0 && g_trace_words != nullptr)                                 \
-            g_trace_words[static_cast<size_t>(tile) * 8 + (k)] = wall_clock64();          \
-    } while (0)
-#else
-#define ZVC_TRACE_POINT(tile, k) do { } while (0)
-#endif
-
 __device__ inline unsigned long long load64(const unsigned long long* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -391,12 +370,23 @@ __device__ inline void wave_flush(unsigned char*& gzero, unsigned char* stage, u
             stop -= 2;
         }
     }
-    // one 256-byte aligned block of the destination per store instruction
-    for (int block = first - static_cast<int>((g + first) & 255u); block < stop; block += 256) {
-        const int at = block + 4 * lane;
-        if (at >= first && at < stop)
-            __builtin_nontemporal_store(queue_dword<W>(stage + at),
-                                        reinterpret_cast<unsigned*>(gzero + block) + lane);
+    // one 256-byte aligned block of the destination per store instruction, four blocks at a
+    // time so that the LDS reads of a round are under way together
+    constexpr int kRound = 4;
+    for (int block = first - static_cast<int>((g + first) & 255u); block < stop; block += 256 * kRound) {
+        unsigned v[kRound];
+#pragma unroll
+        for (int j = 0; j < kRound; ++j) {
+            const int at = block + 256 * j + 4 * lane;
+            v[j] = 0u;
+            if (at >= first && at < stop) v[j] = queue_dword<W>(stage + at);
+        }
+#pragma unroll
+        for (int j = 0; j < kRound; ++j) {
+            const int at = block + 256 * j + 4 * lane;
+            if (at >= first && at < stop)
+                __builtin_nontemporal_store(v[j], reinterpret_cast<unsigned*>(gzero + (block + 256 * j)) + lane);
+        }
     }
     if (last) {
         lo = end;
@@ -520,50 +510,63 @@ __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
         }
         bb -= kWaveSize;
     }
-    // Counts of tiles lo .. t-1, a pair per 8-byte load (lo is a multiple of 64:
-    // pairs are aligned).  A lane adds up its pairs in order as far as they are
-    // published; a later round asks again only for what was missing, so the
-    // waiting re-reads no more than the newest lines of counts.
-    int next = lo + 2 * lane;      // the lane's first pair not added yet
+    // Counts of tiles lo .. t-1, a pair per 8-byte load (lo is a multiple of the
+    // block size: pairs are aligned), kScanBatch loads per lane in flight at a time
+    // (256 tiles a batch; asking for more at once reads more of the newest counts while they are still being written, which measures slower).  The
+    // loads of a batch are added in order as far as everything they cover is
+    // published; a later round asks again only from the first load that found
+    // something missing, so the waiting re-reads no more than the newest counts.
+    constexpr int kScanBatch = 2;
+    constexpr int kLoadTiles = 2 * kWaveSize;     // tiles covered by one load of the wave
+    int done_to = lo;              // wave-uniform: the counts of tiles lo .. done_to-1 are in `sum`
     unsigned sum = 0;              // a lane adds few counts, each below 2^16
     unsigned polls = 0;
-    while (true) {
-        int hole = -1;
-#pragma unroll 1
-        for (int i = next; i < t; i += 2 * kWaveSize) {
-            const unsigned long long pair =
-                load64(reinterpret_cast<const unsigned long long*>(counts + i));
-            const unsigned c0 = static_cast<unsigned>(pair);
-            const unsigned c1 = i + 1 < t ? static_cast<unsigned>(pair >> 32) : kCountValid;
-            if (hole >= 0) continue;
-            if (c0 & c1 & kCountValid) {
+    while (done_to < t) {
+        unsigned long long pair[kScanBatch];
+#pragma unroll
+        for (int k = 0; k < kScanBatch; ++k) {
+            const int i = done_to + k * kLoadTiles + 2 * lane;
+            pair[k] = i < t ? load64(reinterpret_cast<const unsigned long long*>(counts + i))
+                            : (static_cast<unsigned long long>(kCountValid) << 32) | kCountValid;
+        }
+        int complete = 0;          // leading loads of the batch that found everything published
+        int hole = -1;             // wave-uniform: the first tile found unpublished
+#pragma unroll
+        for (int k = 0; k < kScanBatch; ++k) {
+            if (complete != k) continue;          // wave-uniform
+            const int i = done_to + k * kLoadTiles + 2 * lane;
+            const unsigned c0 = static_cast<unsigned>(pair[k]);
+            const unsigned c1 = i + 1 < t ? static_cast<unsigned>(pair[k] >> 32) : kCountValid;
+            const unsigned long long missing = __ballot((c0 & c1 & kCountValid) == 0u);
+            if (!missing) {
                 sum += (c0 & ~kCountValid) + (c1 & ~kCountValid);
-                next = i + 2 * kWaveSize;
+                complete = k + 1;
             } else {
-                hole = (c0 & kCountValid) ? i + 1 : i;
+                const int first = __ffsll(static_cast<long long>(missing)) - 1;
+                hole = done_to + k * kLoadTiles + 2 * first +
+                       ((lane_value(c0, first) & kCountValid) != 0u ? 1 : 0);
             }
         }
-        const unsigned long long holes = __ballot(hole >= 0);
-        if (!holes)   // (halves, so that no partial sum can overflow whatever the distance walked)
-            return base + wave_sum_small(sum & 0xFFFFu) +
-                   (static_cast<unsigned long long>(wave_sum_small(sum >> 16)) << 16);
+        done_to += complete * kLoadTiles;
+        if (hole < 0) continue;                   // the whole batch was there: the next one, if any
         if (polls < patience) {
             ++polls;
             __builtin_amdgcn_s_sleep(kPollSleep);
             continue;
         }
         // help one unpublished predecessor, then look again without waiting anew
-        const int hole_lane = __ffsll(static_cast<long long>(holes)) - 1;
-        const int q = static_cast<int>(lane_value(static_cast<unsigned>(hole), hole_lane));
-        const unsigned helped_count = count_tile(static_cast<unsigned>(q), lane);
+        const unsigned helped_count = count_tile(static_cast<unsigned>(hole), lane);
         unsigned old = 0;
         if (lane == 0) {
-            old = atomicMax(counts + q, kCountValid | helped_count);  // same value as the owner's
+            old = atomicMax(counts + hole, kCountValid | helped_count);  // same value as the owner's
             atomicAdd(&hdr->helped, 1ull);
         }
         // the atomic has returned, so it has been performed before any lane polls again
         asm volatile("" : : "v"(old) : "memory");
     }
+    // (halves, so that no partial sum can overflow whatever the distance walked)
+    return base + wave_sum_small(sum & 0xFFFFu) +
+           (static_cast<unsigned long long>(wave_sum_small(sum >> 16)) << 16);
 }
 
 // Encoder clean-up, see WsHeader::finish.  finish_arrive() is called by lane 0
@@ -682,12 +685,12 @@ __device__ __forceinline__ void set_lane(unsigned& v, unsigned s) {
 }
 
 // Count of kept elements of input tile q, by one wave (scan self-help).
-template <int W, int CH, bool RELU, bool SPLIT>
+template <int W, int CH, int WV, bool RELU, bool SPLIT>
 struct CountInputTile {
     const unsigned char* in;
     size_t n;
     __device__ unsigned operator()(unsigned q, int lane) const {
-        constexpr unsigned kTileDwords = EncoderGeometry<W, CH>::kTileBytes / 4;
+        constexpr unsigned kTileDwords = EncoderGeometry<W, CH, WV>::kTileBytes / 4;
         const size_t d0 = static_cast<size_t>(q) * kTileDwords;      // inside the tensor: q is a predecessor
         const size_t last = (n * W - 1) / 4;
         const unsigned room = last - d0 < kTileDwords ? static_cast<unsigned>(last - d0) : kTileDwords;
@@ -768,16 +771,16 @@ struct EncoderArgs {
 // masks leave with the values instead of going to a mask area.  The scan is the
 // same: a window's byte offset is 4 x (groups before it) + W x (kept elements
 // before it).
-template <int W, int CH, bool RELU, bool WINDOWED, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
-    using G = EncoderGeometry<W, CH>;
+template <int W, int CH, int WV, bool RELU, bool WINDOWED, bool SPLIT>
+__global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a) {
+    using G = EncoderGeometry<W, CH, WV>;
     constexpr int CG = G::kChunkGroups;
     constexpr int kAhead = CH;                    // all of a wave's loads are in flight from the start (measured: 3-6 % over 8 KB at a time)
     constexpr int kWindowChunks = 4;              // a window of the windowed stream: 1 KB of input
     static_assert(W == 2 || !SPLIT, "only 16-bit elements can sit at an odd half dword");
 
-    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kQueueBytes];
-    __shared__ unsigned s_wave_total[kWaves];
+    __shared__ __align__(16) unsigned char s_stage[WV][G::kQueueBytes];
+    __shared__ unsigned s_wave_total[WV];
     __shared__ unsigned s_arrive;                 // waves arrived << 24 | kept elements so far
     __shared__ unsigned long long s_prefix;
 
@@ -785,7 +788,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
     const unsigned tile = blockIdx.x;
-    ZVC_TRACE_POINT(tile, 0);
     if (tid == 0) s_arrive = 0u;
 
     const size_t wave_elem0 = static_cast<size_t>(tile) * G::kTileElems + static_cast<size_t>(wave) * G::kWaveElems;
@@ -876,7 +878,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
                 q_end += 2u * kept + 4u * chunk_groups;
             }
         }
-        if (TEST && k == 0) ZVC_TRACE_POINT(tile, 1);
     };
     constexpr std::true_type yes{};
     constexpr std::false_type no{};
@@ -943,7 +944,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
         for (int k = 0; k < CH; ++k) cur[k] = 0u;
         lds_barrier();
     }
-    ZVC_TRACE_POINT(tile, 2);
     unsigned wave_total = 0;
 #pragma unroll
     for (int h = 0; h < G::kSteps; ++h) wave_total += step_total[h];
@@ -956,7 +956,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
                                          __HIP_MEMORY_SCOPE_WORKGROUP);
     }
     arrived = uniform(arrived);
-    const bool publisher = (arrived >> 24) == kWaves - 1;
+    const bool publisher = (arrived >> 24) == WV - 1;
     if (publisher && lane == 0)
         store32(a.counts + tile, kCountValid | ((arrived & 0xFFFFFFu) + wave_total));
 
@@ -988,31 +988,23 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
             staged = h + 1;
         }
     });
-    ZVC_TRACE_POINT(tile, 3);
 
     // ---- 4. device-wide exclusive scan, wave 0
     if (wave == 0) {
         unsigned long long ex = 0;
-#ifdef ZVC_SCAN_PRIO
-        __builtin_amdgcn_s_setprio(3);
-#endif
         if (tile != 0) {
-            const CountInputTile<W, CH, RELU, SPLIT> count_tile{a.in, a.n};
+            const CountInputTile<W, CH, WV, RELU, SPLIT> count_tile{a.in, a.n};
             ex = scan_exclusive_prefix(a.counts, a.prefixes, tile, lane, a.patience, a.hdr, count_tile);
         }
         if (lane == 0) s_prefix = ex;
-#ifdef ZVC_SCAN_PRIO
-        __builtin_amdgcn_s_setprio(0);
-#endif
     }
     // the tile's count has reached memory before any wave of the tile goes on (see finish_arrive)
     if (publisher) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_barrier();
-    ZVC_TRACE_POINT(tile, 4);
     const unsigned long long exclusive = uniform(s_prefix);
     unsigned wave_offset = 0, tile_total = 0;
 #pragma unroll
-    for (int v = 0; v < kWaves; ++v) {
+    for (int v = 0; v < WV; ++v) {
         const unsigned t = uniform(s_wave_total[v]);
         if (v < wave) wave_offset += t;
         tile_total += t;
@@ -1055,7 +1047,6 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(EncoderArgs a) {
                 a.offsets[window] = static_cast<unsigned long long>(run_begin - a.values) + window_local;
         }
     }
-    ZVC_TRACE_POINT(tile, 5);
 
     // ---- section 5.4: the compressed size, reported by the last tile
     if (tile == a.num_tiles - 1 && tid == 0) {
@@ -1598,18 +1589,25 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
 constexpr unsigned kDefaultPatience = 2000;
 std::atomic<unsigned> g_patience{kDefaultPatience};
 
-// Tile size of the encoder.  Each tile costs a fixed few nanoseconds of
-// chip-wide time (workgroup launch plus the scan's state traffic), so large
-// tensors use 64 KB tiles; smaller tensors use smaller tiles so that every CU
-// still gets several.  The limits are measured crossover points.
-constexpr size_t kLargeTensorBytes = size_t{56} << 20;
+// Shape of the encoder's tile: chunks per wave x waves per workgroup.  Each tile
+// costs a fixed few nanoseconds of chip-wide time (workgroup launch plus the
+// scan's state traffic), so large tensors use 64 KB tiles; smaller tensors use
+// smaller tiles so that every CU still gets several.  More waves with fewer
+// chunks each shorten a tile's serial work (tests, compaction, flush) at the
+// same tile size.  The limits are measured crossover points.
+struct TileShape {
+    int chunks;   // per wave: 8, 16, 32 or 64
+    int waves;    // per workgroup: 4, 8 or 16
+};
+constexpr size_t kLargeTensorBytes = size_t{384} << 20;
 constexpr size_t kMediumTensorBytes = size_t{12} << 20;
-constexpr int kMinChunks = kMinLoads * 16 * kThreads / (kWaves * kChunkBytes);   // 16 KB tiles: 16
+constexpr TileShape kMinShape{16, 4};             // 16 KB, the smallest tile (sizes the workspace)
+static_assert(kMinShape.chunks * kMinShape.waves * kChunkBytes == kMinLoads * 16 * kThreads, "smallest tile");
 
-inline int choose_chunks(size_t n, int w, bool split) {
-    if (split) return kMinChunks;
+inline TileShape choose_shape(size_t n, int w, bool split) {
+    if (split) return kMinShape;
     const size_t bytes = n * static_cast<size_t>(w);
-    return bytes >= kLargeTensorBytes ? 64 : bytes >= kMediumTensorBytes ? 32 : kMinChunks;
+    return bytes >= kLargeTensorBytes ? TileShape{64, 4} : bytes >= kMediumTensorBytes ? TileShape{32, 4} : kMinShape;
 }
 
 // The decoder's waves are independent, so its tile only sets how many staging
@@ -1622,7 +1620,7 @@ inline int choose_decoder_loads(size_t, int, bool aligned) {
 
 enum class Encoder { kPlain, kRelu, kWindowed };
 
-template <int W, int CH, bool SPLIT>
+template <int W, int CH, int WV, bool SPLIT>
 void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
                         unsigned* masks, unsigned char* values, ScanState st,
                         unsigned long long* d_bytes, unsigned tiles, size_t groups,
@@ -1630,16 +1628,16 @@ void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* i
     const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
                            groups, g_patience.load(std::memory_order_relaxed),
                            scan_state_bytes(tiles), cap_values, offsets};
-    const dim3 grid(tiles), block(kThreads);
+    const dim3 grid(tiles), block(WV * kWaveSize);
     switch (mode) {
         case Encoder::kPlain:
-            hipLaunchKernelGGL((compress_kernel<W, CH, false, false, SPLIT>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((compress_kernel<W, CH, WV, false, false, SPLIT>), grid, block, 0, stream, args);
             break;
         case Encoder::kRelu:
-            hipLaunchKernelGGL((compress_kernel<W, CH, true, false, SPLIT>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((compress_kernel<W, CH, WV, true, false, SPLIT>), grid, block, 0, stream, args);
             break;
         case Encoder::kWindowed:
-            hipLaunchKernelGGL((compress_kernel<W, CH, false, true, SPLIT>), grid, block, 0, stream, args);
+            hipLaunchKernelGGL((compress_kernel<W, CH, WV, false, true, SPLIT>), grid, block, 0, stream, args);
             break;
     }
 }
@@ -1662,22 +1660,25 @@ void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                        interleave);
 }
 
-// Picks the instantiation for (w, chunks per wave).  16-bit elements at an odd
-// half dword always use the smallest tile.
+// Picks the instantiation for (w, tile shape).  16-bit elements at an odd half
+// dword always use the smallest tile.  False if there is no such kernel.
 template <typename... Args>
-void launch_compress(int w, int chunks, bool split, Args... args) {
+bool launch_compress(int w, TileShape shape, bool split, Args... args) {
     if (split) {
-        launch_compress_as<2, kMinChunks, true>(args...);
-    } else if (chunks == 64) {
-        if (w == 4) launch_compress_as<4, 64, false>(args...);
-        else launch_compress_as<2, 64, false>(args...);
-    } else if (chunks == 32) {
-        if (w == 4) launch_compress_as<4, 32, false>(args...);
-        else launch_compress_as<2, 32, false>(args...);
-    } else {
-        if (w == 4) launch_compress_as<4, kMinChunks, false>(args...);
-        else launch_compress_as<2, kMinChunks, false>(args...);
+        launch_compress_as<2, kMinShape.chunks, kMinShape.waves, true>(args...);
+        return true;
     }
+#define ZVC_SHAPE_CASE(C, V)                                          \
+    if (shape.chunks == C && shape.waves == V) {                      \
+        if (w == 4) launch_compress_as<4, C, V, false>(args...);      \
+        else launch_compress_as<2, C, V, false>(args...);             \
+        return true;                                                  \
+    }
+    ZVC_SHAPE_CASE(64, 4)
+    ZVC_SHAPE_CASE(32, 4)
+    ZVC_SHAPE_CASE(16, 4)
+#undef ZVC_SHAPE_CASE
+    return false;
 }
 
 template <typename... Args>
@@ -1721,19 +1722,20 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
         return hip_ok(hipGetLastError());
     }
     const bool split = !aligned_to(d_in, 4);        // 16-bit elements at an odd half dword
-    const int chunks = choose_chunks(n, w, split);
-    const size_t tiles = div_up(n * static_cast<size_t>(w), static_cast<size_t>(kWaves) * chunks * kChunkBytes);
+    const TileShape shape = choose_shape(n, w, split);
+    const size_t tiles = div_up(n * static_cast<size_t>(w), static_cast<size_t>(shape.waves) * shape.chunks * kChunkBytes);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     // the scan state is zero between calls: the kernel cleans up after itself
     const size_t groups = div_up(n, 32);
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
     unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    launch_compress(w, chunks, split, mode, stream, in, n, masks,
+    if (!launch_compress(w, shape, split, mode, stream, in, n, masks,
                     mode == Encoder::kWindowed ? static_cast<unsigned char*>(d_out) : values,
                     scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups,
                     !bounded ? ~0ull : out_cap - (mode == Encoder::kWindowed ? 0 : 4 * groups),
-                    reinterpret_cast<unsigned long long*>(d_offsets));
+                    reinterpret_cast<unsigned long long*>(d_offsets)))
+        return ZVC_E_ARG;
     return hip_ok(hipGetLastError());
 }
 
@@ -1852,14 +1854,6 @@ zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream) {
     if (ws < kHeaderBytes) return ZVC_E_WORKSPACE;
     return launch_reset(d_ws, (ws - kHeaderBytes) / 8 * 8, stream);
 }
-
-#ifdef ZVC_TRACE
-// d_words: 8 * tiles device words, or null to switch tracing off.
-zvc_status zvc_trace_set(void* d_words) {
-    return hipMemcpyToSymbol(HIP_SYMBOL(g_trace_words), &d_words, sizeof(d_words)) == hipSuccess
-               ? ZVC_OK : ZVC_E_HIP;
-}
-#endif
 
 void zvc_set_lookback_patience(unsigned polls) {
     g_patience.store(polls, std::memory_order_relaxed);
