@@ -134,6 +134,25 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
 zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream);
 
+/* zvc_compress for callers that cannot allocate or pass a workspace (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * scan state lives in an array inside the library's code object, one copy per
+ * GPU, ZVC_STATIC_SCRATCH_BYTES of device memory that the GPU holds until the
+ * process ends.  Same stream, same arguments and errors as zvc_compress without
+ * d_ws / ws; n * w may be at most ZVC_STATIC_MAX_BYTES (more: ZVC_E_WORKSPACE,
+ * nothing enqueued).  Allocates nothing: no hipMalloc, no hipFree, no host
+ * allocation; the first call on a GPU looks the array's address up (with that
+ * GPU current, as for every call: the stream must belong to the current
+ * device).  All calls on one GPU share the array: two calls that may run at the
+ * same time on one GPU (different streams without an ordering between them)
+ * race and give wrong streams; order them.  Every call leaves the array in its
+ * initial all-zero state; only after a call's kernel was aborted is it not, and
+ * then this entry point must not be used again in the process. */
+#define ZVC_STATIC_MAX_BYTES ((size_t)1 << 30)
+#define ZVC_STATIC_SCRATCH_BYTES ((size_t)320 << 10)
+zvc_status zvc_compress_static(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                               uint64_t* d_bytes, hipStream_t stream);
+
 /* Fused ReLU + compression: d_in holds PRE-activation values and the stream
  * written is exactly the one zvc_compress would write for ReLU(d_in), without
  * the dense ReLU output ever being stored (section 4: the zeros that ZVC

@@ -36,6 +36,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
 #include <cstdint>
 #include <cstring>
 #include <type_traits>
@@ -1700,9 +1701,11 @@ void launch_decompress(int w, int loads, bool aligned, Args... args) {
 
 // `bounded`: out_cap may be anything from the size of the mask area up; the
 // kernel then writes only runs that end inside it.
+// `scan_state_only`: the workspace need only hold the header and the scan state
+// of this call's tiles (the library's own scratch array, which no decoder uses).
 zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n, int w, void* d_out,
                          size_t out_cap, uint64_t* d_bytes, uint64_t* d_offsets, void* d_ws, size_t ws,
-                         hipStream_t stream) {
+                         hipStream_t stream, bool scan_state_only = false) {
     if (w != 2 && w != 4) return ZVC_E_WIDTH;
     if (d_bytes == nullptr || ((d_in == nullptr || d_out == nullptr) && n != 0)) return ZVC_E_ARG;
     if (!aligned_to(d_in, static_cast<size_t>(w)) || !aligned_to(d_out, 4) ||
@@ -1712,7 +1715,8 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
     if (out_cap < (bounded ? zvc_mask_bytes(n) : worst)) return ZVC_E_CAPACITY;
     if (ranges_overlap(d_in, n * static_cast<size_t>(w), d_out, out_cap < worst ? out_cap : worst))
         return ZVC_E_ARG;
-    if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
+    if (!scan_state_only)
+        if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
     unsigned long long* out_bytes = reinterpret_cast<unsigned long long*>(d_bytes);
     if (n == 0) {
         hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out_bytes, 0ull);
@@ -1725,6 +1729,7 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
     const TileShape shape = choose_shape(n, w, split);
     const size_t tiles = div_up(n * static_cast<size_t>(w), static_cast<size_t>(shape.waves) * shape.chunks * kChunkBytes);
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
+    if (scan_state_only && kHeaderBytes + scan_state_bytes(tiles) > ws) return ZVC_E_WORKSPACE;
     // the scan state is zero between calls: the kernel cleans up after itself
     const size_t groups = div_up(n, 32);
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
@@ -1769,6 +1774,32 @@ zvc_status offload_impl(Encoder mode, const void* d_in, size_t n, int w, void* d
     }
     (void)hipEventDestroy(ev);
     return st;
+}
+
+// Scratch of zvc_compress_static: header and scan state for tensors of up to
+// ZVC_STATIC_MAX_BYTES.  Zero when the code object is loaded, which is the
+// state zvc_workspace_init gives a caller's workspace, and every call leaves it
+// zero again.  Each GPU holds its own copy at its own address.
+constexpr size_t kStaticScratchBytes = ZVC_STATIC_SCRATCH_BYTES;   // covers 16 KB tiles (the smallest) up to the limit
+static_assert(kHeaderBytes + 4 * (ZVC_STATIC_MAX_BYTES / (kMinLoads * 16 * kThreads)) + 8 * (ZVC_STATIC_MAX_BYTES / (kMinLoads * 16 * kThreads) / kBlockTiles) + 512 <= ZVC_STATIC_SCRATCH_BYTES, "scratch holds the scan state of the largest call");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];           // device address of `scratch` on each GPU, once looked up
+
+// Device address of the current GPU's copy of `scratch` (looked up once per GPU).
+zvc_status static_scratch(void** ptr) {
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return ZVC_E_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return ZVC_E_HIP;
+        g_scratch_ptr[device] = p;
+    }
+    *ptr = g_scratch_ptr[device];
+    return ZVC_OK;
 }
 
 }  // namespace
@@ -1898,6 +1929,16 @@ zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t o
                         uint64_t* d_bytes, void* d_ws, size_t ws, hipStream_t stream) {
     return compress_impl(Encoder::kPlain, false, d_in, n, w, d_out, out_cap, d_bytes, nullptr, d_ws, ws,
                          stream);
+}
+
+zvc_status zvc_compress_static(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
+                               uint64_t* d_bytes, hipStream_t stream) {
+    if (w != 2 && w != 4) return ZVC_E_WIDTH;
+    if (n > ZVC_STATIC_MAX_BYTES / static_cast<size_t>(w)) return ZVC_E_WORKSPACE;
+    void* ws = nullptr;
+    if (zvc_status st = static_scratch(&ws)) return st;
+    return compress_impl(Encoder::kPlain, false, d_in, n, w, d_out, out_cap, d_bytes, nullptr, ws,
+                         kStaticScratchBytes, stream, true);
 }
 
 zvc_status zvc_relu_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,

@@ -27,7 +27,8 @@ EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
            "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
            "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream",
-           "zvc_window_compress", "zvc_window_decompress", "zvc_compress_bounded")
+           "zvc_window_compress", "zvc_window_decompress", "zvc_compress_bounded",
+           "zvc_compress_static")
 
 _lib = None
 
@@ -65,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_compressed_size.argtypes = [vp, sz, ci, vp, vp, sz, vp]
     lib.zvc_compress.restype = ci
     lib.zvc_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
+    lib.zvc_compress_static.restype = ci
+    lib.zvc_compress_static.argtypes = [vp, sz, ci, vp, sz, vp, vp]
     lib.zvc_window_count.restype = sz
     lib.zvc_window_count.argtypes = [sz, ci]
     lib.zvc_window_check_stream.restype = ci
@@ -186,6 +189,18 @@ def zvc_compress(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor, ws: 
     _check(load().zvc_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
                                d_bytes.data_ptr(), ws.data_ptr(), ws.numel(),
                                _stream_handle(stream)), "zvc_compress")
+
+
+STATIC_MAX_BYTES = 1 << 30   # ZVC_STATIC_MAX_BYTES of include/zvc.h
+
+
+def zvc_compress_static(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor, stream=None,
+                        n: Optional[int] = None) -> None:
+    """zvc_compress without a workspace argument: the scan state lives in an array inside the
+    library (for callers that cannot allocate).  Calls on one GPU must not overlap."""
+    n = x.numel() if n is None else n
+    _check(load().zvc_compress_static(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
+                                      d_bytes.data_ptr(), _stream_handle(stream)), "zvc_compress_static")
 
 
 def zvc_relu_compress(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tensor, ws: torch.Tensor,
