@@ -30,12 +30,13 @@
  *     caller owns every buffer; the library allocates no device memory and
  *     keeps no pointer after the call's work has completed.
  *   - d_in / d_out of the uncompressed tensor must be aligned to w bytes; the
- *     compressed buffer must be aligned to 4 bytes.  16-byte alignment of the
- *     uncompressed tensor selects the fast kernels; anything less still works.
+ *     compressed buffer must be aligned to 4 bytes.  The decoders are fastest
+ *     with a 16-byte aligned d_out, the encoders with a 4-byte aligned d_in
+ *     (which only 16-bit elements can miss); anything less still works.
  *   - input and output ranges must not overlap.
- *   - reads are made in aligned 16-byte chunks: a kernel may read the whole
- *     aligned 16-byte chunk that holds the first or the last byte of a buffer
- *     it is given (such a chunk never straddles a page, so this touches no
+ *   - reads are made in aligned chunks of 4 or 16 bytes: a kernel may read the
+ *     whole aligned 16-byte chunk that holds the first or the last byte of a
+ *     buffer it is given (such a chunk never straddles a page, so this touches no
  *     memory the bytes themselves do not), and ignores what is not the buffer's.
  *     Nothing is ever written outside the output ranges.
  *   - device work is enqueued on the given stream and the call returns
@@ -100,8 +101,10 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
  * section 5.1) lets a tile wait for its predecessors' counts.  After `polls`
  * fruitless polls the waiting tile computes the missing count itself, so the
  * wait always ends.  Default 2000 (about a millisecond); 0 makes every wait
- * help at once, which tests use to exercise that path.  Process-wide. */
-void zvc_set_lookback_patience(unsigned polls);
+ * help at once, which tests use to exercise that path.  The setting belongs to
+ * the workspace (a word in its header, written on `stream`; zvc_workspace_init
+ * restores the default) and applies to the encoder calls that use it. */
+zvc_status zvc_workspace_set_lookback_patience(void* d_ws, unsigned polls, hipStream_t stream);
 
 /* Number of times, since zvc_workspace_init, that a waiting tile computed a
  * predecessor's count itself.  Synchronous 8-byte device-to-host copy; call it
@@ -265,7 +268,10 @@ zvc_status zvc_relu_offload(const void* d_in, size_t n, int w, void* d_stage, si
 
 /* Prefetch, the mirror of zvc_offload: enqueues the host-to-device copy of
  * `bytes` bytes from h_pinned into d_stage on `copy`, then the decompression
- * into d_out on `compute`, ordered after the copy.  No host wait. */
+ * into d_out on `compute`, ordered after the copy.  No host wait.  The copy
+ * overwrites d_stage as soon as `copy` gets to it: if earlier work on `compute`
+ * (a previous zvc_prefetch's decompression, say) still reads d_stage, the
+ * caller must make `copy` wait for that work first, or use another buffer. */
 zvc_status zvc_prefetch(const void* h_pinned, uint64_t bytes, size_t n, int w, void* d_stage,
                         size_t stage_cap, void* d_out, void* d_ws, size_t ws, hipStream_t copy,
                         hipStream_t compute);

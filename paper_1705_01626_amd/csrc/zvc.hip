@@ -35,8 +35,9 @@
 
 #include <hip/hip_runtime.h>
 
-#include <atomic>
 #include <mutex>
+#include <tuple>
+#include <utility>
 #include <cstdint>
 #include <cstring>
 #include <type_traits>
@@ -52,6 +53,8 @@ constexpr size_t kHeaderBytes = 256 + 128 * (kFinishLanes + 1);  // header, then
 constexpr int kMinLoads = 4;                  // smallest tile: 16 KB (sizes the workspace)
 constexpr int kStageLoads = 4;                // 16-byte loads a wave stages through LDS at a time
 constexpr int kBlockTiles = 256;              // one running prefix is published per 256 tiles
+constexpr int kMaxDevices = 64;                // GPUs per process that per-GPU host state is kept for
+constexpr unsigned kDefaultPatience = 2000;   // polls a waiting tile makes before it computes a missing count itself
 constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
 
 // A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
@@ -111,7 +114,8 @@ struct EncoderGeometry {
 
 // Workspace header.  Lives at the start of the caller's workspace.
 struct WsHeader {
-    unsigned long long pad0[2];
+    unsigned long long patience_plus_one;   // 0: default; else polls before a waiting tile helps itself, plus one
+    unsigned long long pad0;
     unsigned long long size_word;  // compressed size for zvc_offload's read-back
     unsigned long long helped;     // predecessor counts computed by a waiting tile since the workspace's init
     unsigned long long pad[28];
@@ -151,8 +155,9 @@ inline size_t prefixes_bytes(size_t tiles) { return 8 * div_up(tiles, kBlockTile
 inline size_t scan_state_bytes(size_t tiles) {
     return counts_bytes(tiles) + div_up(prefixes_bytes(tiles), 256) * 256;
 }
-// the decoder pre-pass arrays follow the encoder's scan state (which is kept
-// zeroed between calls and must not be scribbled on)
+// the decoder pre-pass arrays sit at the end of the workspace, clear of the
+// encoder's scan state (which is kept zeroed between calls and must not be
+// scribbled on)
 inline size_t pad256(size_t b) { return div_up(b, 256) * 256; }
 inline size_t decoder_area_bytes(size_t chunks) {   // chunk_prefix, chunk_total, unit_end
     return pad256(8 * chunks) + pad256(4 * chunks) + pad256(4 * 128 * chunks);
@@ -491,8 +496,7 @@ __device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetch
 template <class CountTile>
 __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
                                                            const unsigned long long* prefixes,
-                                                           unsigned tile, int lane,
-                                                           unsigned patience, WsHeader* hdr,
+                                                           unsigned tile, int lane, WsHeader* hdr,
                                                            const CountTile& count_tile) {
     const int t = static_cast<int>(tile);
     // nearest published block prefix
@@ -521,7 +525,7 @@ __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
     constexpr int kLoadTiles = 2 * kWaveSize;     // tiles covered by one load of the wave
     int done_to = lo;              // wave-uniform: the counts of tiles lo .. done_to-1 are in `sum`
     unsigned sum = 0;              // a lane adds few counts, each below 2^16
-    unsigned polls = 0;
+    unsigned polls = 0, patience = 0;
     while (done_to < t) {
         unsigned long long pair[kScanBatch];
 #pragma unroll
@@ -550,6 +554,10 @@ __device__ inline unsigned long long scan_exclusive_prefix(unsigned* counts,
         }
         done_to += complete * kLoadTiles;
         if (hole < 0) continue;                   // the whole batch was there: the next one, if any
+        if (polls == 0) {                         // the first fruitless poll: how many may follow
+            const unsigned long long p = uniform(load64(&hdr->patience_plus_one));
+            patience = p != 0 ? static_cast<unsigned>(p - 1) : kDefaultPatience;
+        }
         if (polls < patience) {
             ++polls;
             __builtin_amdgcn_s_sleep(kPollSleep);
@@ -735,7 +743,6 @@ struct EncoderArgs {
     unsigned long long* d_bytes;
     unsigned num_tiles;
     size_t num_groups;
-    unsigned patience;
     size_t state_bytes;
     unsigned long long cap_values;   // bytes that may be written at `values`
     unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
@@ -995,7 +1002,7 @@ __global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a)
         unsigned long long ex = 0;
         if (tile != 0) {
             const CountInputTile<W, CH, WV, RELU, SPLIT> count_tile{a.in, a.n};
-            ex = scan_exclusive_prefix(a.counts, a.prefixes, tile, lane, a.patience, a.hdr, count_tile);
+            ex = scan_exclusive_prefix(a.counts, a.prefixes, tile, lane, a.hdr, count_tile);
         }
         if (lane == 0) s_prefix = ex;
     }
@@ -1556,13 +1563,27 @@ inline bool ranges_overlap(const void* a, size_t an, const void* b, size_t bn) {
 
 inline zvc_status hip_ok(hipError_t e) { return e == hipSuccess ? ZVC_OK : ZVC_E_HIP; }
 
+// Kernel launch that reports its own status (hipGetLastError after a <<<>>> launch
+// would also report, and clear, an earlier error of the calling thread).
+template <typename... Params, size_t... I>
+hipError_t launch_impl(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
+                       std::tuple<Params...>& values, std::index_sequence<I...>) {
+    void* pointers[] = {static_cast<void*>(&std::get<I>(values))...};
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, pointers, 0, stream);
+}
+template <typename... Params, typename... Args>
+hipError_t launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args... args) {
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<Params...> values{static_cast<Params>(args)...};
+    return launch_impl(kernel, grid, block, stream, values, std::index_sequence_for<Params...>{});
+}
+
 // Zeroes the header and the first state_bytes bytes of scan state.
 zvc_status launch_reset(void* d_ws, size_t state_bytes, hipStream_t stream) {
     const size_t words = (kHeaderBytes + state_bytes) / 8;
     const unsigned blocks = static_cast<unsigned>(div_up(words, 256) < 1024 ? div_up(words, 256) : 1024);
-    hipLaunchKernelGGL(reset_kernel, dim3(blocks), dim3(256), 0, stream,
-                       static_cast<unsigned long long*>(d_ws), words);
-    return hip_ok(hipGetLastError());
+    return hip_ok(launch(reset_kernel, dim3(blocks), dim3(256), stream,
+                         static_cast<unsigned long long*>(d_ws), words));
 }
 
 // Where the scan state of a call with `tiles` tiles lives inside the workspace.
@@ -1585,10 +1606,6 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
     return ZVC_OK;
 }
 
-// Polls a waiting tile makes before it computes a missing predecessor's count
-// itself.  A poll is one memory round trip (about a microsecond).
-constexpr unsigned kDefaultPatience = 2000;
-std::atomic<unsigned> g_patience{kDefaultPatience};
 
 // Shape of the encoder's tile: chunks per wave x waves per workgroup.  Each tile
 // costs a fixed few nanoseconds of chip-wide time (workgroup launch plus the
@@ -1611,40 +1628,29 @@ inline TileShape choose_shape(size_t n, int w, bool split) {
     return bytes >= kLargeTensorBytes ? TileShape{64, 4} : bytes >= kMediumTensorBytes ? TileShape{32, 4} : kMinShape;
 }
 
-// The decoder's waves are independent, so its tile only sets how many staging
-// steps a wave does one after the other: one step (16 KB tiles) measures best
-// at every size.
-inline int choose_decoder_loads(size_t, int, bool aligned) {
-    if (!aligned) return kMinLoads;
-    return kMinLoads;
-}
-
 enum class Encoder { kPlain, kRelu, kWindowed };
 
 template <int W, int CH, int WV, bool SPLIT>
-void launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
+hipError_t launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
                         unsigned* masks, unsigned char* values, ScanState st,
                         unsigned long long* d_bytes, unsigned tiles, size_t groups,
                         unsigned long long cap_values, unsigned long long* offsets) {
     const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
-                           groups, g_patience.load(std::memory_order_relaxed),
-                           scan_state_bytes(tiles), cap_values, offsets};
+                           groups, scan_state_bytes(tiles), cap_values, offsets};
     const dim3 grid(tiles), block(WV * kWaveSize);
     switch (mode) {
         case Encoder::kPlain:
-            hipLaunchKernelGGL((compress_kernel<W, CH, WV, false, false, SPLIT>), grid, block, 0, stream, args);
-            break;
+            return launch(compress_kernel<W, CH, WV, false, false, SPLIT>, grid, block, stream, args);
         case Encoder::kRelu:
-            hipLaunchKernelGGL((compress_kernel<W, CH, WV, true, false, SPLIT>), grid, block, 0, stream, args);
-            break;
+            return launch(compress_kernel<W, CH, WV, true, false, SPLIT>, grid, block, stream, args);
         case Encoder::kWindowed:
-            hipLaunchKernelGGL((compress_kernel<W, CH, WV, false, true, SPLIT>), grid, block, 0, stream, args);
-            break;
+            return launch(compress_kernel<W, CH, WV, false, true, SPLIT>, grid, block, stream, args);
     }
+    return hipErrorInvalidValue;
 }
 
 template <int W, int LOADS, bool ALIGNED>
-void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
+hipError_t launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
                           unsigned char* out, const unsigned* unit_end,
                           const unsigned long long* chunk_prefix, size_t groups) {
@@ -1656,47 +1662,36 @@ void launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
     // kernel): interleaved where it measures faster, 2-15 % below a twelfth and 2-5 %
     // above a third of the elements stored; in between the plain order is 1 % ahead.
     const bool interleave = (avail < n / 12 || avail > n / 3) && n * W >= (size_t{64} << 20);   // (no gain on small tensors)
-    hipLaunchKernelGGL((decompress_kernel<W, LOADS, ALIGNED>), grid, dim3(kThreads), 0, stream,
-                       masks, values, avail, n, out, unit_end, chunk_prefix, groups, stream_values,
-                       interleave);
+    return launch(decompress_kernel<W, LOADS, ALIGNED>, grid, dim3(kThreads), stream,
+                  masks, values, avail, n, out, unit_end, chunk_prefix, groups, stream_values, interleave);
 }
 
 // Picks the instantiation for (w, tile shape).  16-bit elements at an odd half
-// dword always use the smallest tile.  False if there is no such kernel.
+// dword always use the smallest tile.
 template <typename... Args>
-bool launch_compress(int w, TileShape shape, bool split, Args... args) {
-    if (split) {
-        launch_compress_as<2, kMinShape.chunks, kMinShape.waves, true>(args...);
-        return true;
-    }
-#define ZVC_SHAPE_CASE(C, V)                                          \
-    if (shape.chunks == C && shape.waves == V) {                      \
-        if (w == 4) launch_compress_as<4, C, V, false>(args...);      \
-        else launch_compress_as<2, C, V, false>(args...);             \
-        return true;                                                  \
-    }
+hipError_t launch_compress(int w, TileShape shape, bool split, Args... args) {
+    if (split) return launch_compress_as<2, kMinShape.chunks, kMinShape.waves, true>(args...);
+#define ZVC_SHAPE_CASE(C, V)                                                    \
+    if (shape.chunks == C && shape.waves == V)                                  \
+        return w == 4 ? launch_compress_as<4, C, V, false>(args...)             \
+                      : launch_compress_as<2, C, V, false>(args...);
     ZVC_SHAPE_CASE(64, 4)
     ZVC_SHAPE_CASE(32, 4)
     ZVC_SHAPE_CASE(16, 4)
 #undef ZVC_SHAPE_CASE
-    return false;
+    return hipErrorInvalidValue;   // choose_shape() returns nothing else
 }
 
+// The decoder has one tile size (its waves are independent; one staging step per
+// wave measures best at every size) and a path for outputs that are not
+// 16-byte aligned.
 template <typename... Args>
-void launch_decompress(int w, int loads, bool aligned, Args... args) {
-    if (!aligned) {
-        if (w == 4) launch_decompress_as<4, kMinLoads, false>(args...);
-        else launch_decompress_as<2, kMinLoads, false>(args...);
-    } else if (loads == 16) {
-        if (w == 4) launch_decompress_as<4, 16, true>(args...);
-        else launch_decompress_as<2, 16, true>(args...);
-    } else if (loads == 8) {
-        if (w == 4) launch_decompress_as<4, 8, true>(args...);
-        else launch_decompress_as<2, 8, true>(args...);
-    } else {
-        if (w == 4) launch_decompress_as<4, 4, true>(args...);
-        else launch_decompress_as<2, 4, true>(args...);
-    }
+hipError_t launch_decompress(int w, bool aligned, Args... args) {
+    if (!aligned)
+        return w == 4 ? launch_decompress_as<4, kMinLoads, false>(args...)
+                      : launch_decompress_as<2, kMinLoads, false>(args...);
+    return w == 4 ? launch_decompress_as<4, kMinLoads, true>(args...)
+                  : launch_decompress_as<2, kMinLoads, true>(args...);
 }
 
 // `bounded`: out_cap may be anything from the size of the mask area up; the
@@ -1719,11 +1714,11 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
         if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
     unsigned long long* out_bytes = reinterpret_cast<unsigned long long*>(d_bytes);
     if (n == 0) {
-        hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out_bytes, 0ull);
-        if (mode == Encoder::kWindowed)
-            hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream,
-                               reinterpret_cast<unsigned long long*>(d_offsets), 0ull);
-        return hip_ok(hipGetLastError());
+        hipError_t e = launch(write_word_kernel, dim3(1), dim3(1), stream, out_bytes, 0ull);
+        if (e == hipSuccess && mode == Encoder::kWindowed)
+            e = launch(write_word_kernel, dim3(1), dim3(1), stream,
+                       reinterpret_cast<unsigned long long*>(d_offsets), 0ull);
+        return hip_ok(e);
     }
     const bool split = !aligned_to(d_in, 4);        // 16-bit elements at an odd half dword
     const TileShape shape = choose_shape(n, w, split);
@@ -1735,13 +1730,24 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
     unsigned* masks = static_cast<unsigned*>(d_out);
     unsigned char* values = static_cast<unsigned char*>(d_out) + 4 * groups;
-    if (!launch_compress(w, shape, split, mode, stream, in, n, masks,
+    return hip_ok(launch_compress(w, shape, split, mode, stream, in, n, masks,
                     mode == Encoder::kWindowed ? static_cast<unsigned char*>(d_out) : values,
                     scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups,
                     !bounded ? ~0ull : out_cap - (mode == Encoder::kWindowed ? 0 : 4 * groups),
-                    reinterpret_cast<unsigned long long*>(d_offsets)))
-        return ZVC_E_ARG;
-    return hip_ok(hipGetLastError());
+                    reinterpret_cast<unsigned long long*>(d_offsets)));
+}
+
+// One event per host thread and GPU for ordering a copy stream after a compute
+// stream (or the other way round), created at first use and kept: creating and
+// destroying one per call costs several microseconds per tensor.
+hipEvent_t thread_event() {
+    thread_local hipEvent_t events[kMaxDevices] = {};
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+    if (events[device] == nullptr &&
+        hipEventCreateWithFlags(&events[device], hipEventDisableTiming) != hipSuccess)
+        events[device] = nullptr;
+    return events[device];
 }
 
 zvc_status offload_impl(Encoder mode, const void* d_in, size_t n, int w, void* d_stage,
@@ -1759,8 +1765,8 @@ zvc_status offload_impl(Encoder mode, const void* d_in, size_t n, int w, void* d
         return st;
     if (hipMemcpyAsync(h_bytes, d_size, 8, hipMemcpyDeviceToHost, compute) != hipSuccess)
         return ZVC_E_HIP;
-    hipEvent_t ev;
-    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return ZVC_E_HIP;
+    hipEvent_t ev = thread_event();
+    if (ev == nullptr) return ZVC_E_HIP;
     zvc_status st = ZVC_OK;
     if (hipEventRecord(ev, compute) != hipSuccess || hipEventSynchronize(ev) != hipSuccess) {
         st = ZVC_E_HIP;
@@ -1772,7 +1778,6 @@ zvc_status offload_impl(Encoder mode, const void* d_in, size_t n, int w, void* d
                                            copy) != hipSuccess)
             st = ZVC_E_HIP;
     }
-    (void)hipEventDestroy(ev);
     return st;
 }
 
@@ -1784,7 +1789,6 @@ constexpr size_t kStaticScratchBytes = ZVC_STATIC_SCRATCH_BYTES;   // covers 16 
 static_assert(kHeaderBytes + 4 * (ZVC_STATIC_MAX_BYTES / (kMinLoads * 16 * kThreads)) + 8 * (ZVC_STATIC_MAX_BYTES / (kMinLoads * 16 * kThreads) / kBlockTiles) + 512 <= ZVC_STATIC_SCRATCH_BYTES, "scratch holds the scan state of the largest call");
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
-constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices];           // device address of `scratch` on each GPU, once looked up
 
@@ -1886,8 +1890,12 @@ zvc_status zvc_workspace_init(void* d_ws, size_t ws, hipStream_t stream) {
     return launch_reset(d_ws, (ws - kHeaderBytes) / 8 * 8, stream);
 }
 
-void zvc_set_lookback_patience(unsigned polls) {
-    g_patience.store(polls, std::memory_order_relaxed);
+zvc_status zvc_workspace_set_lookback_patience(void* d_ws, unsigned polls, hipStream_t stream) {
+    if (d_ws == nullptr) return ZVC_E_ARG;
+    if (!aligned_to(d_ws, 256)) return ZVC_E_ALIGN;
+    WsHeader* hdr = static_cast<WsHeader*>(d_ws);
+    return hip_ok(launch(write_word_kernel, dim3(1), dim3(1), stream, &hdr->patience_plus_one,
+                         static_cast<unsigned long long>(polls) + 1ull));
 }
 
 zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count) {
@@ -1904,8 +1912,7 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
     if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
     unsigned long long* out = reinterpret_cast<unsigned long long*>(d_bytes);
     if (n == 0) {
-        hipLaunchKernelGGL(write_word_kernel, dim3(1), dim3(1), 0, stream, out, 0ull);
-        return hip_ok(hipGetLastError());
+        return hip_ok(launch(write_word_kernel, dim3(1), dim3(1), stream, out, 0ull));
     }
     WsHeader* hdr = static_cast<WsHeader*>(d_ws);   // accumulators are zero between calls
     const unsigned char* in = static_cast<const unsigned char*>(d_in);
@@ -1915,14 +1922,9 @@ zvc_status zvc_compressed_size(const void* d_in, size_t n, int w, uint64_t* d_by
     const dim3 grid(static_cast<unsigned>(tiles)), block(kThreads);
     const unsigned nt = static_cast<unsigned>(tiles);
     const bool al = aligned_to(d_in, 16);
-    if (w == 4) {
-        if (al) hipLaunchKernelGGL((count_kernel<4, true>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
-        else hipLaunchKernelGGL((count_kernel<4, false>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
-    } else {
-        if (al) hipLaunchKernelGGL((count_kernel<2, true>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
-        else hipLaunchKernelGGL((count_kernel<2, false>), grid, block, 0, stream, in, n, hdr, out, groups, nt);
-    }
-    return hip_ok(hipGetLastError());
+    const auto kernel = w == 4 ? (al ? count_kernel<4, true> : count_kernel<4, false>)
+                               : (al ? count_kernel<2, true> : count_kernel<2, false>);
+    return hip_ok(launch(kernel, grid, block, stream, in, n, hdr, out, groups, nt));
 }
 
 zvc_status zvc_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
@@ -2001,18 +2003,10 @@ zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, cons
     const bool al = aligned_to(d_out, 16);
     // dense streams of large ranges decode 3-8 % faster in the interleaved order, others slower
     const bool interleave = stream_bytes / 3 > n * static_cast<size_t>(w) / 4 && out_bytes >= (size_t{64} << 20);
-    const auto launch = [&](auto kernel) {
-        hipLaunchKernelGGL(kernel, grid, block, 0, stream, in, stream_bytes, offs, n, groups, first_window,
-                           num_windows, out, interleave);
-    };
-    if (w == 4) {
-        if (al) launch(window_decode_kernel<4, true>);
-        else launch(window_decode_kernel<4, false>);
-    } else {
-        if (al) launch(window_decode_kernel<2, true>);
-        else launch(window_decode_kernel<2, false>);
-    }
-    return hip_ok(hipGetLastError());
+    const auto kernel = w == 4 ? (al ? window_decode_kernel<4, true> : window_decode_kernel<4, false>)
+                               : (al ? window_decode_kernel<2, true> : window_decode_kernel<2, false>);
+    return hip_ok(launch(kernel, grid, block, stream, in, static_cast<unsigned long long>(stream_bytes), offs, n,
+                         groups, first_window, num_windows, out, interleave));
 }
 
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,
@@ -2025,29 +2019,28 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     if (zvc_status st = check_workspace(d_ws, ws, n, w)) return st;
     if (n == 0) return ZVC_OK;
     const bool al = aligned_to(d_out, 16);
-    const int loads = choose_decoder_loads(n, w, al);
     // a multiple of 8 workgroups: the interleaved order deals the parts out in rounds of 8
-    const size_t tiles = div_up(tiles_for(n, w, loads), 8) * 8;
+    const size_t tiles = div_up(tiles_for(n, w, kMinLoads), 8) * 8;
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     const size_t groups = div_up(n, 32);
     const size_t chunks = div_up(groups, kChunkMasks);
     if (chunks > 0xFFFFFFFFull) return ZVC_E_ARG;
-    // pre-pass arrays live after the encoder's scan state and need no reset
-    unsigned char* area = static_cast<unsigned char*>(d_ws) + kHeaderBytes +
-                          scan_state_bytes(tiles_for(n, w, kMinLoads));
+    // The pre-pass arrays need no reset.  They sit at the end of the workspace, whatever its
+    // size: an encoder call that this workspace is large enough for keeps its scan state
+    // (which must stay zero between calls) below them, whichever call came first.
+    unsigned char* area = static_cast<unsigned char*>(d_ws) + (ws - decoder_area_bytes(chunks)) / 256 * 256;
     unsigned long long* chunk_prefix = reinterpret_cast<unsigned long long*>(area);
     unsigned* chunk_total = reinterpret_cast<unsigned*>(area + pad256(8 * chunks));
     unsigned* unit_end = reinterpret_cast<unsigned*>(area + pad256(8 * chunks) + pad256(4 * chunks));
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
-    hipLaunchKernelGGL(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), 0,
-                       stream, masks, groups, static_cast<unsigned>(n % 32), unit_end, chunk_total,
-                       chunk_prefix, static_cast<WsHeader*>(d_ws), static_cast<unsigned>(chunks));
-    if (hipGetLastError() != hipSuccess) return ZVC_E_HIP;
+    if (launch(mask_prefix_kernel, dim3(static_cast<unsigned>(chunks)), dim3(kThreads), stream, masks,
+               groups, static_cast<unsigned>(n % 32), unit_end, chunk_total, chunk_prefix,
+               static_cast<WsHeader*>(d_ws), static_cast<unsigned>(chunks)) != hipSuccess)
+        return ZVC_E_HIP;
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
-    launch_decompress(w, loads, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values,
-                      avail, n, static_cast<unsigned char*>(d_out), unit_end, chunk_prefix, groups);
-    return hip_ok(hipGetLastError());
+    return hip_ok(launch_decompress(w, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values, avail, n,
+                                    static_cast<unsigned char*>(d_out), unit_end, chunk_prefix, groups));
 }
 
 zvc_status zvc_offload(const void* d_in, size_t n, int w, void* d_stage, size_t stage_cap,
@@ -2078,12 +2071,10 @@ zvc_status zvc_prefetch(const void* h_pinned, uint64_t bytes, size_t n, int w, v
     if (hipMemcpyAsync(d_stage, h_pinned, bytes, hipMemcpyHostToDevice, copy) != hipSuccess)
         return ZVC_E_HIP;
     if (copy != compute) {
-        hipEvent_t ev;
-        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return ZVC_E_HIP;
-        const bool ok = hipEventRecord(ev, copy) == hipSuccess &&
-                        hipStreamWaitEvent(compute, ev, 0) == hipSuccess;
-        (void)hipEventDestroy(ev);
-        if (!ok) return ZVC_E_HIP;
+        hipEvent_t ev = thread_event();
+        if (ev == nullptr || hipEventRecord(ev, copy) != hipSuccess ||
+            hipStreamWaitEvent(compute, ev, 0) != hipSuccess)
+            return ZVC_E_HIP;
     }
     return zvc_decompress(d_stage, bytes, n, w, d_out, d_ws, ws, compute);
 }

@@ -13,8 +13,7 @@ from typing import Optional, Tuple
 import torch
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-# ZVC_LIBRARY selects another build of the same library (tuning experiments)
-LIBRARY = os.environ.get("ZVC_LIBRARY") or os.path.join(_PKG, "libzvc.so")
+LIBRARY = os.path.join(_PKG, "libzvc.so")
 
 STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_WORKSPACE",
                 "ZVC_E_ALIGN", "ZVC_E_HIP", "ZVC_E_CORRUPT")
@@ -25,7 +24,7 @@ STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_W
 EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
-           "zvc_prefetch", "zvc_set_lookback_patience", "zvc_workspace_self_help_count",
+           "zvc_prefetch", "zvc_workspace_set_lookback_patience", "zvc_workspace_self_help_count",
            "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream",
            "zvc_window_compress", "zvc_window_decompress", "zvc_compress_bounded",
            "zvc_compress_static")
@@ -88,8 +87,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_relu_offload.argtypes = [vp, sz, ci, vp, sz, vp, sz, vp, vp, sz, vp, vp]
     lib.zvc_prefetch.restype = ci
     lib.zvc_prefetch.argtypes = [vp, u64, sz, ci, vp, sz, vp, vp, sz, vp, vp]
-    lib.zvc_set_lookback_patience.restype = None
-    lib.zvc_set_lookback_patience.argtypes = [ctypes.c_uint]
+    lib.zvc_workspace_set_lookback_patience.restype = ci
+    lib.zvc_workspace_set_lookback_patience.argtypes = [vp, ctypes.c_uint, vp]
     lib.zvc_workspace_self_help_count.restype = ci
     lib.zvc_workspace_self_help_count.argtypes = [vp, vp]
     _lib = lib
@@ -143,8 +142,9 @@ def zvc_window_check_stream(h_stream: torch.Tensor, nbytes: int, h_offsets: torc
     return int(load().zvc_window_check_stream(h_stream.data_ptr(), nbytes, h_offsets.data_ptr(), n, w))
 
 
-def zvc_set_lookback_patience(polls: int) -> None:
-    load().zvc_set_lookback_patience(int(polls))
+def zvc_workspace_set_lookback_patience(ws: torch.Tensor, polls: int, stream=None) -> None:
+    _check(load().zvc_workspace_set_lookback_patience(ws.data_ptr(), int(polls), _stream_handle(stream)),
+           "zvc_workspace_set_lookback_patience")
 
 
 def zvc_workspace_self_help_count(ws: torch.Tensor) -> int:

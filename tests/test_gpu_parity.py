@@ -213,23 +213,25 @@ def test_decompress_never_reads_past_comp_bytes(oracle):
 def test_scan_wait_that_helps_itself(oracle):
     """With zero patience every wait in the device-wide scan computes the
     missing predecessor's count itself.  Results must not change, and every
-    kernel still exits normally."""
-    try:
-        zvc.zvc_set_lookback_patience(0)
-        helped = 0
-        for w, n in ((4, 3000001), (2, 5000003), (4, 6000001), (4, (1 << 24) + 12345)):   # all three tile sizes
-            x = random_tensor(n, w, 0.45, seed=w + n)
-            ws = zvc.new_workspace(n, w, DEV)
-            res = assert_parity(x, oracle, "zero-patience scan", ws)
-            helped += zvc.zvc_workspace_self_help_count(res["ws"])
-        say("self-help events in the last decompress calls: %d" % helped)
-    finally:
-        zvc.zvc_set_lookback_patience(2000)
+    kernel still exits normally.  The setting belongs to the workspace."""
+    helped = 0
+    for w, n in ((4, 3000001), (2, 5000003), (4, 6000001), (4, (1 << 24) + 12345), (4, 100 * (1 << 20) + 3)):   # all three tile sizes
+        x = random_tensor(n, w, 0.45, seed=w + n)
+        ws = zvc.new_workspace(n, w, DEV)
+        zvc.zvc_workspace_set_lookback_patience(ws, 0)
+        res = assert_parity(x, oracle, "zero-patience scan", ws)
+        helped += zvc.zvc_workspace_self_help_count(res["ws"])
+        # another workspace keeps the default
+        assert_parity(x[: n // 3], oracle, "default patience beside it")
+    say("self-help events: %d" % helped)
+    assert helped > 0
 
 
-def test_no_self_help_in_normal_runs(oracle):
+def test_self_help_is_rare_in_normal_runs(oracle):
     """Default patience: predecessors publish long before a waiting tile gives
-    up, so no count is ever computed twice (informational guard on dispatch order)."""
+    up.  How often a count is computed twice depends on dispatch order and on
+    what else the GPU is doing, so this reports the number and only checks that
+    the fallback is not the normal path."""
     n, w = (1 << 24) + 4096, 4
     x = random_tensor(n, w, 0.5, seed=77)
     ws = zvc.new_workspace(n, w, DEV)
@@ -238,12 +240,30 @@ def test_no_self_help_in_normal_runs(oracle):
     say("self-help counter, compress")
     zvc.zvc_compress(x, comp, d_bytes, ws)
     torch.cuda.synchronize()
-    assert zvc.zvc_workspace_self_help_count(ws) == 0
+    helped = zvc.zvc_workspace_self_help_count(ws)
+    say("self-help events at default patience: %d" % helped)
+    tiles = (n * w + (32 << 10) - 1) // (32 << 10)
+    assert helped <= tiles // 100
     out = torch.empty_like(x)
     zvc.zvc_decompress(comp, int(d_bytes.item()), out, ws)
     torch.cuda.synchronize()
-    assert zvc.zvc_workspace_self_help_count(ws) == 0
     assert torch.equal(out, x)
+
+
+def test_small_decode_then_large_encode_on_one_workspace(oracle):
+    """The decoder's scratch arrays must not land where a later, larger encoder
+    call on the same workspace keeps its scan state."""
+    big_n, small_n, w = 40 * (1 << 20) + 5, 300007, 4
+    ws = zvc.new_workspace(big_n, w, DEV)
+    small = random_tensor(small_n, w, 0.999, seed=5)      # dense: large decoder prefix words
+    res = assert_parity(small, oracle, "small tensor on a large workspace", ws)
+    big = random_tensor(big_n, w, 0.3, seed=6)
+    assert_parity(big, oracle, "large tensor after it", ws)
+    out = torch.empty_like(small)
+    zvc.zvc_decompress(res["comp"], res["bytes"], out, ws)
+    assert_parity(big, oracle, "large tensor again, after a small decode", ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, small)
 
 
 def test_decoder_many_chunks_and_reuse(oracle):
