@@ -11,7 +11,11 @@ reported beside it).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
-Prints ONE JSON line.  Only one GPU is used; --gpus above 1 is refused.
+Prints ONE JSON line.  Without --workload the headline is the largest
+single-tensor workload of the baseline list (sweep_0.5: fp32 64x64x224x224,
+822 MB, half non-zero) and the line also carries `per_workload`: every other
+single-tensor workload and the 16-tensor offload stream, each timed the same
+way (fewer repetitions).  Only one GPU is used; --gpus above 1 is refused.
 """
 from __future__ import annotations
 
@@ -27,6 +31,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+HEADLINE = "sweep_0.5"
 
 WORKLOADS = ("conv_small", "conv1_style", "sweep_0.05", "sweep_0.2", "sweep_0.5", "sweep_0.8",
              "sweep_1.0", "layout_fp32_nchw", "layout_fp32_nhwc", "layout_fp32_chwn",
@@ -48,7 +53,7 @@ def make_workload(name: str, seed: int, device):
         key = name[len("layout_"):]
         return (workloads.layout_variants(seed, device)[key],
                 "128x256x28x28 blurred-field 30%% density, %s" % key)
-    raise SystemExit("unknown workload %r (choose from %s)" % (name, ", ".join(WORKLOADS)))
+    raise SystemExit("unknown workload %r (choose from %s, vgg_offload)" % (name, ", ".join(WORKLOADS)))
 
 
 def event_timed(fn, reps: int, torch) -> float:
@@ -64,12 +69,129 @@ def event_timed(fn, reps: int, torch) -> float:
     return start.elapsed_time(stop) / reps
 
 
+class Codec:
+    """One tensor set up for timing: zvc_compress / zvc_decompress (or the fused
+    ReLU encoder, or the windowed stream) over rotating copies of the buffers.
+
+    Cold inputs: the calls rotate over copies of the buffers whose inputs add up
+    to more than 512 MB, twice the Infinity Cache, so that no call finds its data
+    cached by the previous one (`warm` keeps one set)."""
+
+    def __init__(self, x, torch, zvc, relu=False, windowed=False, warm=False, seed=0):
+        self.torch, self.zvc = torch, zvc
+        self.relu, self.windowed = relu, windowed
+        dev = x.device
+        x_in = x
+        if relu:
+            from paper_1705_01626_amd import workloads
+            x_in = workloads.pre_activation(x.float(), seed + 1).to(x.dtype)
+            x = torch.relu(x_in)          # what the round trip must give back
+        self.expect = x
+        self.n, self.w = x.numel(), x.element_size()
+        n, w = self.n, self.w
+        self.windows = zvc.zvc_window_count(n, w) if windowed else 0
+        self.ws = zvc.new_workspace(n, w, dev)
+        self.d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
+        copies = 1 if warm else max(1, -(-(512 << 20) // max(n * w, 1)))
+        self.copies = min(copies, 64)
+        self.sets = []
+        for k in range(self.copies):
+            xi = x_in if k == 0 else x_in.clone()
+            comp = zvc.new_compressed_buffer(n, w, dev)
+            offsets = torch.zeros(self.windows + 1, dtype=torch.int64, device=dev) if windowed else None
+            self.sets.append((xi, comp, torch.empty_like(x), offsets))
+        self.turn_c = self.turn_d = 0
+        for _ in range(self.copies):      # every compressed buffer holds the stream before any decode is timed
+            self.compress()
+        self.nbytes = int(self.d_bytes.item())
+        groups = (n + 31) // 32
+        self.nnz = (self.nbytes - 4 * groups) // w
+        torch.cuda.synchronize()
+
+    def compress(self):
+        xi, comp, _, offsets = self.sets[self.turn_c % self.copies]
+        self.turn_c += 1
+        if self.windowed:
+            self.zvc.zvc_window_compress(xi, comp, offsets, self.d_bytes, self.ws)
+        elif self.relu:
+            self.zvc.zvc_relu_compress(xi, comp, self.d_bytes, self.ws)
+        else:
+            self.zvc.zvc_compress(xi, comp, self.d_bytes, self.ws)
+
+    def decompress(self):
+        _, comp, out, offsets = self.sets[self.turn_d % self.copies]
+        self.turn_d += 1
+        if self.windowed:
+            self.zvc.zvc_window_decompress(comp, self.nbytes, offsets, self.n, 0, self.windows, out)
+        else:
+            self.zvc.zvc_decompress(comp, self.nbytes, out, self.ws)
+
+    def step(self):
+        self.compress()
+        self.decompress()
+
+    def verify(self):
+        """Every set once more, whatever the step count was; the round trip must be the identity."""
+        torch = self.torch
+        self.turn_c = self.turn_d = 0
+        for _, _, out, _ in self.sets:
+            out.view(torch.uint8).fill_(0xEE)
+        for _ in range(self.copies):
+            self.step()
+        torch.cuda.synchronize()
+        for _, _, out, _ in self.sets:
+            assert torch.equal(out.view(torch.uint8), self.expect.view(torch.uint8)), "round trip differs"
+        assert int(self.d_bytes.item()) == self.nbytes
+
+    @property
+    def uncompressed(self):
+        return self.n * self.w
+
+    @property
+    def algorithmic(self):
+        """Bytes the method itself must move, either direction: compress reads n*w and writes the
+        stream, decompress is the mirror."""
+        return self.n * self.w + self.nbytes
+
+    def row(self, ms_c, ms_d):
+        alg = self.algorithmic
+        return {"uncompressed_bytes": self.uncompressed, "compressed_bytes": self.nbytes,
+                "density": round(self.nnz / self.n, 6),
+                "ratio": round(self.uncompressed / self.nbytes, 4),
+                "algorithmic_bytes": alg,
+                "compress_ms": round(ms_c, 5), "decompress_ms": round(ms_d, 5),
+                "compress_frac": round(alg / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "decompress_frac": round(alg / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "buffers": self.copies}
+
+
+def cpu_info():
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return model, os.cpu_count() or 1, usable
+
+
 def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool = False,
                  windowed: bool = False):
     """The oracle as it stands, single thread, on the same bytes: whole-tensor
     compress + decompress round trips until about `budget_s` seconds are spent.
     With `relu` the encoder is the oracle's fused ReLU + ZVC (ReLU into a
-    temporary, then the plain encoder)."""
+    temporary, then the plain encoder).  A second figure runs the same oracle on
+    all usable host cores, one group-aligned slice of the tensor per thread (each
+    slice its own stream), for about a third of the budget."""
+    import threading
+
     import numpy as np
     from oracle import zvc_ref
     lib = zvc_ref.load()
@@ -97,24 +219,56 @@ def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool 
         reps += 1
         best = dt if best is None else min(best, dt)
     if relu:
-        from oracle import zvc_ref as ref
-        assert np.array_equal(back[: n * w], ref.relu(host_bytes[: n * w], w))
+        assert np.array_equal(back[: n * w], zvc_ref.relu(host_bytes[: n * w], w))
     else:
         assert np.array_equal(back[: n * w], host_bytes[: n * w])
-    return {"value": round(2.0 * n * w / best / 1e9, 4), "unit": "GB/s", "cores": 1,
-            "kind": "oracle",
-            "sample": "whole tensor (%d bytes), %d compress+decompress round trips, best" % (n * w, reps)}
+    model, logical, usable = cpu_info()
+    result = {"value": round(2.0 * n * w / best / 1e9, 4), "unit": "GB/s", "cores": 1,
+              "kind": "oracle",
+              "sample": "whole tensor (%d bytes), %d compress+decompress round trips, best" % (n * w, reps),
+              "cpu_model": model, "nproc": logical, "usable_cores": usable}
+    if not relu and not windowed and usable > 1:
+        threads = usable
+        per_thread = (n // threads) // 32 * 32
+        if per_thread > 0:
+            slices = [(t * per_thread, per_thread if t < threads - 1 else n - t * per_thread)
+                      for t in range(threads)]
+
+            def work(lo, cnt):
+                src = host_bytes[lo * w:]
+                g0 = lo // 32
+                c = comp[4 * g0 + lo * w:]
+                lib.zvc_ref_compress_stream(vp(src.ctypes.data), cnt, w, vp(c.ctypes.data))
+                lib.zvc_ref_decompress_stream(vp(c.ctypes.data), cnt, w, vp(back[lo * w:].ctypes.data))
+
+            best_all, spent_all, reps_all = None, 0.0, 0
+            while reps_all < 1 or (spent_all < budget_s / 3 and reps_all < 20):
+                pool = [threading.Thread(target=work, args=s) for s in slices]
+                t0 = time.perf_counter()
+                for t in pool:
+                    t.start()
+                for t in pool:
+                    t.join()
+                dt = time.perf_counter() - t0
+                spent_all += dt
+                reps_all += 1
+                best_all = dt if best_all is None else min(best_all, dt)
+            assert np.array_equal(back[: n * w], host_bytes[: n * w])
+            result["all_cores"] = {"value": round(2.0 * n * w / best_all / 1e9, 4), "unit": "GB/s",
+                                   "cores": threads,
+                                   "sample": "the same tensor in %d group-aligned slices, one thread and one "
+                                             "stream each, %d round trips, best" % (threads, reps_all)}
+    return result
 
 
-def run_offload_stream(args) -> int:
+def offload_stream(args, torch, zvc):
     """The VGG-16-style offload stream (16 ReLU outputs, batch 64): per-tensor codec
-    rates, the aggregate, and the two-stream pipeline compress -> D2H -> H2D -> decompress
-    against the same copies done uncompressed (the offload the paper starts from)."""
-    import torch
-    from paper_1705_01626_amd import workloads, zvc
+    rates on cold buffers, the aggregate, and the two-stream pipeline compress -> D2H ->
+    H2D -> decompress against the same copies done uncompressed (the offload the paper
+    starts from), with the paper's bandwidth model fed with the measured numbers."""
+    from paper_1705_01626_amd import cdma_model, workloads
 
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
     specs = workloads.vgg_offload_stream()
     xs = [workloads.vgg_layer(s, i, args.seed, dev) for i, s in enumerate(specs)]
     caps = [zvc.zvc_max_compressed_bytes(x.numel(), 4) for x in xs]
@@ -123,7 +277,6 @@ def run_offload_stream(args) -> int:
     plain = [torch.empty(x.numel(), dtype=torch.float32, pin_memory=True) for x in xs]
     outs = [torch.empty_like(x) for x in xs]
     h_bytes = torch.zeros(1, dtype=torch.int64, pin_memory=True)
-    d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
     ws = zvc.new_workspace(max(x.numel() for x in xs), 4, dev)
     compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -155,7 +308,7 @@ def run_offload_stream(args) -> int:
     sizes = offload_all()
     prefetch_all(sizes)
     plain_round_trip()
-    reps = max(1, min(args.steps, 5))
+    reps = max(1, min(args.steps, 3))
     t_off = t_pre = t_pd2h = t_ph2d = 0.0
     for _ in range(reps):
         torch.cuda.synchronize()
@@ -173,50 +326,38 @@ def run_offload_stream(args) -> int:
     for x, o in zip(xs, outs):
         assert torch.equal(x, o), "offload round trip differs"
     t_off, t_pre, t_pd2h, t_ph2d = (t / reps for t in (t_off, t_pre, t_pd2h, t_ph2d))
+    del stages, pinned, plain, outs
 
-    # codec alone, per tensor, HIP events on the current stream
-    layers, tc_all, td_all = [], 0.0, 0.0
-    for spec, x, st, o, nb in zip(specs, xs, stages, outs, sizes):
-        k = max(5, args.steps)
-        ms_c = event_timed(lambda: zvc.zvc_compress(x, st, d_bytes, ws), k, torch)
-        ms_d = event_timed(lambda: zvc.zvc_decompress(st, nb, o, ws), k, torch)
-        ub = x.numel() * 4
-        layers.append({"layer": spec.name, "bytes": ub, "density": round(spec.density, 4),
-                       "ratio": round(ub / nb, 3), "compress_ms": round(ms_c, 5),
-                       "decompress_ms": round(ms_d, 5),
-                       "compress_hbm_frac": round((ub + nb) / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                       "decompress_hbm_frac": round((ub + nb) / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
+    # codec alone, per tensor, on cold buffers (rotating copies), HIP events on the current stream
+    layers, tc_all, td_all, alg_all = [], 0.0, 0.0, 0
+    k = max(5, min(args.steps, 10))
+    for spec, x, nb in zip(specs, xs, sizes):
+        codec = Codec(x, torch, zvc)
+        assert codec.nbytes == nb
+        reps_l = max(k, codec.copies)
+        ms_c = event_timed(codec.compress, reps_l, torch)
+        ms_d = event_timed(codec.decompress, reps_l, torch)
+        row = codec.row(ms_c, ms_d)
+        row["layer"] = spec.name
+        layers.append(row)
         tc_all += ms_c
         td_all += ms_d
+        alg_all += codec.algorithmic
+        del codec
+        torch.cuda.empty_cache()
     total_in = sum(x.numel() * 4 for x in xs)
     total_out = sum(sizes)
-    # the paper's bandwidth model (section 6) fed with what was just measured: kernel
-    # times per tensor, the pinned-copy rate of this machine, and a size read-back per tensor
-    from paper_1705_01626_amd import cdma_model
     link_gbps = total_in / t_pd2h / 1e9
-    model_layers = [{"bytes": l["bytes"], "compressed_bytes": nb, "compress_s": l["compress_ms"] * 1e-3}
+    model_layers = [{"bytes": l["uncompressed_bytes"], "compressed_bytes": nb, "compress_s": l["compress_ms"] * 1e-3}
                     for l, nb in zip(layers, sizes)]
     model = cdma_model.predict(model_layers, link_gbps, host_gap_s=20e-6)
-    model_out = {"link_GBps": round(link_gbps, 2), "host_gap_us_per_tensor": 20,
-                 "predicted_offload_ms": round(model["offload_s"] * 1e3, 3),
-                 "predicted_speedup": round(model["speedup"], 3),
-                 "link_bound_ms": round(model["link_bound_s"] * 1e3, 3),
-                 "compute_stream_ms": round(model["compute_stream_s"] * 1e3, 3),
-                 "max_COMP_BW_needed_GBps": round(model["max_comp_bw_needed_gbps"], 1),
-                 "min_encoder_read_GBps": round(model["min_encoder_read_gbps"], 1),
-                 "layers_that_starve_the_link": model["layers_that_starve_the_link"],
-                 "avg_codec_hbm_GBps": round(model["avg_codec_hbm_gbps"], 1),
-                 "measured_over_predicted": round(t_off / model["offload_s"], 3)}
-    print(json.dumps({
-        "metric": "ZVC offload stream (VGG-16-style, batch 64): pipeline and codec rates",
-        "value": round(2.0 * total_in / ((tc_all + td_all) * 1e-3) / 1e9, 2), "unit": "GB/s",
-        "n_gpus": 1, "steps": reps, "warmup": 1, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "u32", "data": "synthetic",
-        "config": {"workload": "vgg_offload", "tensors": 16, "uncompressed_bytes": total_in,
-                   "compressed_bytes": total_out, "stream_ratio": round(total_in / total_out, 4)},
-        "codec_aggregate": {"compress_ms": round(tc_all, 4), "decompress_ms": round(td_all, 4),
-                            "hbm_frac": round((total_in + total_out) * 2 / ((tc_all + td_all) * 1e-3)
-                                              / 1e9 / HBM_PEAK_GBPS, 4)},
+    return {
+        "workload": "vgg_offload", "tensors": len(xs), "uncompressed_bytes": total_in,
+        "compressed_bytes": total_out, "ratio": round(total_in / total_out, 4),
+        "algorithmic_bytes": alg_all,
+        "compress_ms": round(tc_all, 4), "decompress_ms": round(td_all, 4),
+        "compress_frac": round(alg_all / (tc_all * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "decompress_frac": round(alg_all / (td_all * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "pipeline": {"offload_ms": round(t_off * 1e3, 3), "prefetch_ms": round(t_pre * 1e3, 3),
                      "uncompressed_d2h_ms": round(t_pd2h * 1e3, 3),
                      "uncompressed_h2d_ms": round(t_ph2d * 1e3, 3),
@@ -224,21 +365,32 @@ def run_offload_stream(args) -> int:
                      "prefetch_speedup": round(t_ph2d / t_pre, 3),
                      "d2h_GBps_compressed_bytes": round(total_out / t_off / 1e9, 2),
                      "d2h_GBps_uncompressed_copy": round(total_in / t_pd2h / 1e9, 2)},
-        "cdma_model": model_out,
-        "layers": layers}))
-    return 0
+        "cdma_model": {"link_GBps": round(link_gbps, 2), "host_gap_us_per_tensor": 20,
+                       "predicted_offload_ms": round(model["offload_s"] * 1e3, 3),
+                       "predicted_speedup": round(model["speedup"], 3),
+                       "link_bound_ms": round(model["link_bound_s"] * 1e3, 3),
+                       "compute_stream_ms": round(model["compute_stream_s"] * 1e3, 3),
+                       "max_COMP_BW_needed_GBps": round(model["max_comp_bw_needed_gbps"], 1),
+                       "min_encoder_read_GBps": round(model["min_encoder_read_gbps"], 1),
+                       "layers_that_starve_the_link": model["layers_that_starve_the_link"],
+                       "avg_codec_hbm_GBps": round(model["avg_codec_hbm_gbps"], 1),
+                       "measured_over_predicted": round(t_off / model["offload_s"], 3)},
+        "layers": layers}
 
 
 def load_traffic(workload: str, direction: str):
     """HBM bytes per launch of one direction ("compress" / "decompress") from the committed
-    rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic.json), or None."""
+    rocprofv3 FETCH_SIZE / WRITE_SIZE runs (profiles/hbm_traffic.json) and where they come
+    from, or (None, None)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if not os.path.exists(path):
-        return None
+        return None, None
     with open(path) as f:
         table = json.load(f)
     entry = table.get(workload)
-    return entry[direction]["total"] if entry else None
+    if not entry:
+        return None, None
+    return entry[direction]["total"], entry.get("source")
 
 
 def main() -> int:
@@ -246,7 +398,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="conv1_style")
+    ap.add_argument("--workload", default=None,
+                    help="one workload only (%s, vgg_offload); default: %s as the headline plus a table "
+                         "of all the others" % (", ".join(WORKLOADS), HEADLINE))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--relu", action="store_true",
                     help="time the fused ReLU + ZVC encoder on pre-activations of the workload "
@@ -259,6 +413,7 @@ def main() -> int:
                          "Infinity Cache); by default the calls rotate over enough copies to exceed 512 MB")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-verify", action="store_true")
+    ap.add_argument("--no-table", action="store_true", help="headline only, no per_workload table")
     ap.add_argument("--counter-pass", action="store_true",
                     help="for rocprofv3 --pmc runs: a few rounds of [plain device copy of the "
                          "tensor, zvc_compress, zvc_decompress] and nothing else")
@@ -268,125 +423,80 @@ def main() -> int:
               "see DESIGN.md for how it would shard); --gpus %d is refused" % args.gpus,
               file=sys.stderr)
         return 2
+    if args.relu and args.windowed:
+        raise SystemExit("bench.py: --relu and --windowed are separate modes")
 
     import torch
     from paper_1705_01626_amd import zvc
 
     zvc.load()  # fails loudly if the HIP library is not built
-    if args.workload == "vgg_offload":
-        return run_offload_stream(args)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    x, described = make_workload(args.workload, args.seed, dev)
-    x_in = x
+    if args.workload == "vgg_offload":
+        r = offload_stream(args, torch, zvc)
+        print(json.dumps({
+            "metric": "ZVC offload stream (VGG-16-style, batch 64): pipeline and codec rates",
+            "value": round(2.0 * r["uncompressed_bytes"] / ((r["compress_ms"] + r["decompress_ms"]) * 1e-3) / 1e9, 2),
+            "unit": "GB/s", "n_gpus": 1, "steps": max(1, min(args.steps, 3)), "warmup": 1,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32",
+            "data": "synthetic", "config": {"workload": "vgg_offload"}, "vgg_offload": r}))
+        return 0
+
+    table = args.workload is None and not (args.no_table or args.relu or args.windowed or args.counter_pass)
+    name = args.workload or HEADLINE
+    x, described = make_workload(name, args.seed, dev)
     if args.relu:
-        from paper_1705_01626_amd import workloads
-        x_in = workloads.pre_activation(x.float(), args.seed + 1).to(x.dtype)
-        x = torch.relu(x_in)          # what the round trip must give back
         described += "; pre-activations (zeros replaced by negative draws), fused ReLU + ZVC encoder"
-    if args.relu and args.windowed:
-        raise SystemExit("bench.py: --relu and --windowed are separate modes")
-    encode = zvc.zvc_relu_compress if args.relu else zvc.zvc_compress
-    n, w = x.numel(), x.element_size()
     if args.windowed:
-        windows = zvc.zvc_window_count(n, w)
-        offsets = torch.zeros(windows + 1, dtype=torch.int64, device=dev)
         described += "; paper-order stream in 1 KB windows with an offset table"
-
-        def encode(t, c, b, s):
-            zvc.zvc_window_compress(t, c, offsets, b, s)
-    ws = zvc.new_workspace(n, w, dev)
-    comp = zvc.new_compressed_buffer(n, w, dev)
-    d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
-    out = torch.empty_like(x)
-
-    encode(x_in, comp, d_bytes, ws)
-    nbytes = int(d_bytes.item())
-    groups = (n + 31) // 32
-    nnz = (nbytes - 4 * groups) // w
-    density = nnz / n
-
-    # Cold inputs: rotate over copies of the buffers whose inputs add up to more than 512 MB,
-    # twice the Infinity Cache, so that no call finds its data cached by the previous one.
-    copies = 1 if args.warm else max(1, -(-(512 << 20) // max(n * w, 1)))
-    copies = min(copies, 64)
-    sets = [(x_in, comp, out, offsets if args.windowed else None)]
-    for _ in range(copies - 1):
-        c2 = torch.empty_like(comp)
-        o2 = offsets.clone() if args.windowed else None
-        xi = x_in.clone()
-        if args.windowed:
-            zvc.zvc_window_compress(xi, c2, o2, d_bytes, ws)
-        else:
-            encode(xi, c2, d_bytes, ws)
-        sets.append((xi, c2, torch.empty_like(x), o2))
-    torch.cuda.synchronize()
-    turn = {"c": 0, "d": 0}
-
-    def compress():
-        xi, c, _, o = sets[turn["c"] % copies]
-        turn["c"] += 1
-        if args.windowed:
-            zvc.zvc_window_compress(xi, c, o, d_bytes, ws)
-        else:
-            encode(xi, c, d_bytes, ws)
-
-    def decompress():
-        _, c, o_t, o = sets[turn["d"] % copies]
-        turn["d"] += 1
-        if args.windowed:
-            zvc.zvc_window_decompress(c, nbytes, o, n, 0, windows, o_t)
-        else:
-            zvc.zvc_decompress(c, nbytes, o_t, ws)
-
-    def step():
-        compress()
-        decompress()
+    codec = Codec(x, torch, zvc, relu=args.relu, windowed=args.windowed, warm=args.warm, seed=args.seed)
+    n, w = codec.n, codec.w
 
     if args.counter_pass:
         # the plain copy (n*w bytes read, n*w bytes written) calibrates the counters
+        out = codec.sets[0][2]
         for _ in range(max(1, args.steps)):
-            out.copy_(x)
-            compress()
-            decompress()
+            out.copy_(codec.expect)
+            codec.compress()
+            codec.decompress()
         torch.cuda.synchronize()
-        print(json.dumps({"counter_pass": True, "workload": args.workload,
-                          "uncompressed_bytes": n * w, "compressed_bytes": nbytes}))
+        print(json.dumps({"counter_pass": True, "workload": name,
+                          "uncompressed_bytes": n * w, "compressed_bytes": codec.nbytes}))
         return 0
 
+    # ---- the timed region: exactly `steps` steps, with HIP events on the launch stream around
+    #      every call so that the dominant kernel's own duration comes from the same region
     for _ in range(args.warmup):
-        step()
+        codec.step()
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for e in marks:
+        e[0].record()
+        codec.compress()
+        e[1].record()
+        codec.decompress()
+        e[2].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
+    ms_c_in_step = sum(e[0].elapsed_time(e[1]) for e in marks) / args.steps
+    ms_d_in_step = sum(e[1].elapsed_time(e[2]) for e in marks) / args.steps
 
-    # per-kernel durations with HIP events on the launch stream
-    ms_c = event_timed(compress, args.steps, torch)
-    ms_d = event_timed(decompress, args.steps, torch)
+    # per-direction call times, the calls of one kind back to back
+    ms_c = event_timed(codec.compress, args.steps, torch)
+    ms_d = event_timed(codec.decompress, args.steps, torch)
     torch.cuda.synchronize()
-
     if not args.no_verify:
-        turn["c"] = turn["d"] = 0
-        for _ in range(copies):      # every set once more, whatever the step count was
-            step()
-        torch.cuda.synchronize()
-        for _, _, o_t, _ in sets:
-            assert torch.equal(o_t.view(torch.uint8), x.view(torch.uint8)), "round trip differs"
-        assert int(d_bytes.item()) == nbytes
+        codec.verify()
 
-    uncompressed = n * w
-    algorithmic = uncompressed + nbytes  # compress: read n*w, write stream; decompress: the mirror
+    uncompressed, algorithmic = codec.uncompressed, codec.algorithmic
     # The roofline kernel is compress_kernel: the one kernel of a zvc_compress call (zero
     # test, masks, scan, compaction, size) and the longest kernel of the step in rocprofv3's
-    # trace; its call time is the kernel plus one launch gap.  zvc_decompress is two kernels
-    # (mask pre-pass + expand) and is reported beside it as a whole call.
-    dominant, ms_dom = "zvc_compress", ms_c
-    achieved = algorithmic / (ms_dom * 1e-3) / 1e9
-    traffic = load_traffic(args.workload, dominant[len("zvc_"):])
+    # trace; the events around the call see the kernel plus one launch gap.  zvc_decompress
+    # is two kernels (mask pre-pass + expand) and is reported beside it as a whole call.
+    achieved = algorithmic / (ms_c_in_step * 1e-3) / 1e9
+    traffic, traffic_source = load_traffic(name, "compress")
     result = {
         "metric": "ZVC compress+decompress GB/s (uncompressed bytes) and % of HBM peak",
         "value": round(2.0 * uncompressed / (ms_per_step * 1e-3) / 1e9, 2),
@@ -400,28 +510,68 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u32" if w == 4 else "u16",
         "data": "synthetic",
-        "config": {"workload": args.workload, "tensor": described, "elements": n,
+        "config": {"workload": name, "tensor": described, "elements": n,
                    "element_bytes": w, "uncompressed_bytes": uncompressed,
-                   "compressed_bytes": nbytes, "density": round(density, 6),
-                   "compression_ratio": round(uncompressed / nbytes, 4), "seed": args.seed,
+                   "compressed_bytes": codec.nbytes, "density": round(codec.nnz / n, 6),
+                   "compression_ratio": round(uncompressed / codec.nbytes, 4), "seed": args.seed,
                    "encoder": "relu+zvc" if args.relu else "zvc",
                    "stream": "windowed" if args.windowed else "planar",
-                   "buffers": "%d rotating set%s (%s)" % (copies, "" if copies == 1 else "s",
+                   "buffers": "%d rotating set%s (%s)" % (codec.copies, "" if codec.copies == 1 else "s",
                                                            "warm" if args.warm else "cold inputs")},
         "compress_GBps": round(uncompressed / (ms_c * 1e-3) / 1e9, 2),
         "decompress_GBps": round(uncompressed / (ms_d * 1e-3) / 1e9, 2),
         "compress_ms": round(ms_c, 5),
         "decompress_ms": round(ms_d, 5),
+        "in_step_ms": {"compress": round(ms_c_in_step, 5), "decompress": round(ms_d_in_step, 5)},
         "hbm_peak_fraction": {"compress": round(algorithmic / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                               "decompress": round(algorithmic / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "kernel": "compress_kernel", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": algorithmic,
-                     "traffic": traffic},
+                     "launch_ms": round(ms_c_in_step, 5),
+                     "timed_with": "HIP events around each zvc_compress call of the timed region",
+                     "traffic": traffic, "traffic_source": traffic_source},
     }
+    host = None
     if not args.no_cpu_baseline:
-        host = x_in.view(torch.uint8).cpu().numpy().reshape(-1)
+        host = codec.sets[0][0].view(torch.uint8).cpu().numpy().reshape(-1)
+    headline_row = codec.row(ms_c, ms_d)
+    del codec, x
+    torch.cuda.empty_cache()
+
+    if table:
+        rows = []
+        reps = max(5, min(args.steps, 20))
+        for other in WORKLOADS:
+            if other == name:
+                row = dict(headline_row)
+            else:
+                xo, _ = make_workload(other, args.seed, dev)
+                c = Codec(xo, torch, zvc)
+                r = max(reps, c.copies)
+                for _ in range(2):
+                    c.step()
+                mc = event_timed(c.compress, r, torch)
+                md = event_timed(c.decompress, r, torch)
+                if not args.no_verify:
+                    c.verify()
+                row = c.row(mc, md)
+                del c, xo
+                torch.cuda.empty_cache()
+            row = {"workload": other, **row}
+            rows.append(row)
+        vgg = offload_stream(args, torch, zvc)
+        vgg_layers = vgg.pop("layers")
+        rows.append({k: vgg[k] for k in ("workload", "tensors", "uncompressed_bytes", "compressed_bytes", "ratio",
+                                           "algorithmic_bytes", "compress_ms", "decompress_ms",
+                                           "compress_frac", "decompress_frac")})
+        result["per_workload"] = rows
+        result["vgg_offload"] = {"pipeline": vgg["pipeline"], "cdma_model": vgg["cdma_model"],
+                                 "layers": [{k: l[k] for k in ("layer", "uncompressed_bytes", "density", "ratio",
+                                                                "compress_ms", "decompress_ms", "compress_frac",
+                                                                "decompress_frac")} for l in vgg_layers]}
+    if host is not None:
         result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu, windowed=args.windowed)
     print(json.dumps(result))
     return 0
