@@ -1077,14 +1077,17 @@ __global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a)
 //   unit_end[u]    = stored elements of the chunk up to and including unit u
 //                    (a unit is 32 masks, 1024 elements),
 //   chunk_total[c] = stored elements of the chunk.
-// The workgroup that finishes last (arrival counters in the header, which it
-// also resets) turns the totals into chunk_prefix[c] = stored elements before
-// chunk c.
+// Unless chunk_prefix is null (few chunks, see kFewChunks), the workgroup that
+// finishes last (arrival counters in the header, which it also resets) turns
+// the totals into chunk_prefix[c] = stored elements before chunk c.
 constexpr int kUnitMasks = 32;
 constexpr int kChunkLoads = 4;                                 // 16-byte loads per thread
 constexpr int kChunkMasks = kThreads * 4 * kChunkLoads;        // 4096 masks = 131072 elements
 constexpr int kChunkUnits = kChunkMasks / kUnitMasks;          // 128
 constexpr int kUnitLanes = kUnitMasks / 4;                     // 8 lanes of one load cover a unit
+// Up to this many chunks (134M elements) the expand kernel's workgroups each add
+// up the chunk totals before their own chunk; above, the pre-pass does it once.
+constexpr unsigned kFewChunks = 1024;
 
 __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     const unsigned* __restrict__ masks, size_t num_groups, unsigned tail,
@@ -1153,6 +1156,13 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
         unit_end[static_cast<size_t>(chunk) * kChunkUnits + tid] =
             incl + (wave == 1 ? s_wave_total[0] : 0u);
 
+    // ---- few chunks: the expand kernel's workgroups add up the totals before theirs
+    //      themselves (a KB or so from L2 each), which costs less than the two memory
+    //      round trips below
+    if (chunk_prefix == nullptr) {
+        if (tid == 0) chunk_total[chunk] = s_wave_total[0] + s_wave_total[1];
+        return;
+    }
     // ---- the last workgroup to get here prefixes the chunk totals
     if (tid == 0) {
         store32(chunk_total + chunk, s_wave_total[0] + s_wave_total[1]);
@@ -1229,7 +1239,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
     unsigned long long values_avail, size_t n, unsigned char* __restrict__ out,
     const unsigned* __restrict__ unit_end, const unsigned long long* __restrict__ chunk_prefix,
-    size_t num_groups, bool stream_values, bool interleave) {
+    const unsigned* __restrict__ chunk_total, size_t num_groups, bool stream_values, bool interleave) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
     constexpr int LPG = G::kLanesPerGroup;
@@ -1253,13 +1263,31 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const size_t part = interleave ? (static_cast<size_t>(tile / 8) * kWaves + wave) * 8 + tile % 8
                                    : static_cast<size_t>(tile) * kWaves + wave;
     const size_t wave_elem0 = part * (static_cast<size_t>(LOADS) * kWaveSize * E);
-    if (wave_elem0 >= n) return;                  // nothing of the tensor in this wave's part
     const size_t wave_group0 = wave_elem0 / 32;
-    const size_t chunk = wave_group0 / kChunkMasks;
+    const size_t chunk = wave_group0 / kChunkMasks;     // the same for all waves of the workgroup
     const unsigned tail = static_cast<unsigned>(n % 32);
 
+    // ---- stored elements before the wave's chunk: from the pre-pass, or (few chunks) the
+    //      workgroup adds up the totals of the chunks before its own
+    unsigned long long before_chunk = 0;
+    if (chunk_prefix == nullptr) {
+        __shared__ unsigned long long s_before;
+        if (tid == 0) s_before = 0ull;
+        unsigned partial = 0;                      // at most 4 totals of at most 2^17 each
+        const size_t before = min(chunk, div_up(num_groups, static_cast<size_t>(kChunkMasks)));   // (a workgroup past the tensor's end)
+        for (size_t c = tid; c < before; c += kThreads) partial += chunk_total[c];
+        const unsigned wave_part = wave_sum_small(partial);
+        lds_barrier();
+        if (lane == 0 && wave_part != 0u)
+            __hip_atomic_fetch_add(&s_before, static_cast<unsigned long long>(wave_part), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+        lds_barrier();
+        before_chunk = s_before;
+    }
+    if (wave_elem0 >= n) return;                  // nothing of the tensor in this wave's part
+    if (chunk_prefix != nullptr) before_chunk = chunk_prefix[chunk];
+
     // ---- everything the steps need from memory, requested up front
-    const unsigned long long before_chunk = chunk_prefix[chunk];
     unsigned m[kSteps], step_begin[kSteps], step_end[kSteps];
 #pragma unroll
     for (int h = 0; h < kSteps; ++h) {
@@ -1649,11 +1677,15 @@ hipError_t launch_compress_as(Encoder mode, hipStream_t stream, const unsigned c
     return hipErrorInvalidValue;
 }
 
+// Tensors below this size never decode in the interleaved order (no gain there).
+inline bool interleaves(size_t n, int w) { return n * static_cast<size_t>(w) >= (size_t{64} << 20); }
+
 template <int W, int LOADS, bool ALIGNED>
 hipError_t launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* masks,
                           const unsigned char* values, unsigned long long avail, size_t n,
                           unsigned char* out, const unsigned* unit_end,
-                          const unsigned long long* chunk_prefix, size_t groups) {
+                          const unsigned long long* chunk_prefix, const unsigned* chunk_total,
+                          size_t groups) {
     // Dense streams (3/4 of the elements stored, or more) are read with the streaming
     // hint: little of a cache line is then shared between waves, and the hint is worth
     // 5 % there; sparser streams are read through the caches (see load16_stream).
@@ -1661,9 +1693,10 @@ hipError_t launch_decompress_as(dim3 grid, hipStream_t stream, const unsigned* m
     // Order in which the parts of the tensor are dealt out to the workgroups (see the
     // kernel): interleaved where it measures faster, 2-15 % below a twelfth and 2-5 %
     // above a third of the elements stored; in between the plain order is 1 % ahead.
-    const bool interleave = (avail < n / 12 || avail > n / 3) && n * W >= (size_t{64} << 20);   // (no gain on small tensors)
+    const bool interleave = (avail < n / 12 || avail > n / 3) && interleaves(n, W);
     return launch(decompress_kernel<W, LOADS, ALIGNED>, grid, dim3(kThreads), stream,
-                  masks, values, avail, n, out, unit_end, chunk_prefix, groups, stream_values, interleave);
+                  masks, values, avail, n, out, unit_end, chunk_prefix, chunk_total, groups, stream_values,
+                  interleave);
 }
 
 // Picks the instantiation for (w, tile shape).  16-bit elements at an odd half
@@ -2029,7 +2062,8 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     // size: an encoder call that this workspace is large enough for keeps its scan state
     // (which must stay zero between calls) below them, whichever call came first.
     unsigned char* area = static_cast<unsigned char*>(d_ws) + (ws - decoder_area_bytes(chunks)) / 256 * 256;
-    unsigned long long* chunk_prefix = reinterpret_cast<unsigned long long*>(area);
+    unsigned long long* chunk_prefix =
+        chunks <= kFewChunks ? nullptr : reinterpret_cast<unsigned long long*>(area);
     unsigned* chunk_total = reinterpret_cast<unsigned*>(area + pad256(8 * chunks));
     unsigned* unit_end = reinterpret_cast<unsigned*>(area + pad256(8 * chunks) + pad256(4 * chunks));
     const unsigned* masks = static_cast<const unsigned*>(d_comp);
@@ -2040,7 +2074,8 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     const unsigned char* values = static_cast<const unsigned char*>(d_comp) + 4 * groups;
     const unsigned long long avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
     return hip_ok(launch_decompress(w, al, dim3(static_cast<unsigned>(tiles)), stream, masks, values, avail, n,
-                                    static_cast<unsigned char*>(d_out), unit_end, chunk_prefix, groups));
+                                    static_cast<unsigned char*>(d_out), unit_end, chunk_prefix, chunk_total,
+                                    groups));
 }
 
 zvc_status zvc_offload(const void* d_in, size_t n, int w, void* d_stage, size_t stage_cap,
