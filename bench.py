@@ -130,6 +130,36 @@ class Codec:
         self.compress()
         self.decompress()
 
+    # The same-run yardsticks: a plain streaming kernel with the traffic of a compress call
+    # (n*w bytes in, the stream's bytes out) and of a decompress call (the mirror), and a plain
+    # device copy of the tensor, on the same rotating buffers.  They write into the `out`
+    # buffers, which hold nothing that is still needed.
+    def reference_compress(self):
+        xi, _, out, _ = self.sets[self.turn_c % self.copies]
+        self.turn_c += 1
+        nw = self.n * self.w
+        self.zvc.zvc_reference_stream(xi, nw // 16 * 16, out, min(self.nbytes, nw) // 16 * 16)
+
+    def reference_decompress(self):
+        _, comp, out, _ = self.sets[self.turn_d % self.copies]
+        self.turn_d += 1
+        self.zvc.zvc_reference_stream(comp, self.nbytes // 16 * 16, out, self.n * self.w // 16 * 16)
+
+    def plain_copy(self):
+        xi, _, out, _ = self.sets[self.turn_c % self.copies]
+        self.turn_c += 1
+        out.copy_(xi)
+
+    def references(self, reps):
+        """ms per call of the three yardsticks (each kind back to back, like the codec calls)."""
+        torch = self.torch
+        reps = max(reps, self.copies)
+        for fn in (self.reference_compress, self.reference_decompress, self.plain_copy):
+            fn()
+        return {"compress_traffic_ms": round(event_timed(self.reference_compress, reps, torch), 5),
+                "decompress_traffic_ms": round(event_timed(self.reference_decompress, reps, torch), 5),
+                "device_copy_ms": round(event_timed(self.plain_copy, reps, torch), 5)}
+
     def verify(self):
         """Every set once more, whatever the step count was; the round trip must be the identity."""
         torch = self.torch
@@ -153,7 +183,18 @@ class Codec:
         stream, decompress is the mirror."""
         return self.n * self.w + self.nbytes
 
-    def row(self, ms_c, ms_d):
+    def row(self, ms_c, ms_d, ref=None):
+        alg = self.algorithmic
+        extra = {}
+        if ref is not None:
+            # the plain kernel with the same traffic, and how the codec call compares with it
+            extra = {"plain_kernel_same_traffic_ms": [ref["compress_traffic_ms"], ref["decompress_traffic_ms"]],
+                     "plain_kernel_frac": [round(alg / (ref["compress_traffic_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                           round(alg / (ref["decompress_traffic_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)],
+                     "device_copy_ms": ref["device_copy_ms"]}
+        return {**self._row(ms_c, ms_d), **extra}
+
+    def _row(self, ms_c, ms_d):
         alg = self.algorithmic
         return {"uncompressed_bytes": self.uncompressed, "compressed_bytes": self.nbytes,
                 "density": round(self.nnz / self.n, 6),
@@ -329,7 +370,7 @@ def offload_stream(args, torch, zvc):
     del stages, pinned, plain, outs
 
     # codec alone, per tensor, on cold buffers (rotating copies), HIP events on the current stream
-    layers, tc_all, td_all, alg_all = [], 0.0, 0.0, 0
+    layers, tc_all, td_all, alg_all, ref_c, ref_d = [], 0.0, 0.0, 0, 0.0, 0.0
     k = max(5, min(args.steps, 10))
     for spec, x, nb in zip(specs, xs, sizes):
         codec = Codec(x, torch, zvc)
@@ -337,8 +378,11 @@ def offload_stream(args, torch, zvc):
         reps_l = max(k, codec.copies)
         ms_c = event_timed(codec.compress, reps_l, torch)
         ms_d = event_timed(codec.decompress, reps_l, torch)
-        row = codec.row(ms_c, ms_d)
+        ref = codec.references(reps_l)
+        row = codec.row(ms_c, ms_d, ref)
         row["layer"] = spec.name
+        ref_c += ref["compress_traffic_ms"]
+        ref_d += ref["decompress_traffic_ms"]
         layers.append(row)
         tc_all += ms_c
         td_all += ms_d
@@ -358,6 +402,9 @@ def offload_stream(args, torch, zvc):
         "compress_ms": round(tc_all, 4), "decompress_ms": round(td_all, 4),
         "compress_frac": round(alg_all / (tc_all * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
         "decompress_frac": round(alg_all / (td_all * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+        "plain_kernel_same_traffic_ms": [round(ref_c, 4), round(ref_d, 4)],
+        "plain_kernel_frac": [round(alg_all / (ref_c * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                              round(alg_all / (ref_d * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)],
         "pipeline": {"offload_ms": round(t_off * 1e3, 3), "prefetch_ms": round(t_pre * 1e3, 3),
                      "uncompressed_d2h_ms": round(t_pd2h * 1e3, 3),
                      "uncompressed_h2d_ms": round(t_ph2d * 1e3, 3),
@@ -489,6 +536,7 @@ def main() -> int:
     torch.cuda.synchronize()
     if not args.no_verify:
         codec.verify()
+    reference = None if (args.relu or args.windowed) else codec.references(max(5, min(args.steps, 20)))
 
     uncompressed, algorithmic = codec.uncompressed, codec.algorithmic
     # The roofline kernel is compress_kernel: the one kernel of a zvc_compress call (zero
@@ -536,7 +584,15 @@ def main() -> int:
     host = None
     if not args.no_cpu_baseline:
         host = codec.sets[0][0].view(torch.uint8).cpu().numpy().reshape(-1)
-    headline_row = codec.row(ms_c, ms_d)
+    if reference is not None:
+        result["reference"] = {
+            **reference,
+            "what": "a plain streaming kernel given the bytes of a compress call (n*w in, the stream out) "
+                    "and of a decompress call (the mirror), and a device copy of the tensor, timed in "
+                    "this run on the same buffers",
+            "compress_frac_of_peak": round(algorithmic / (reference["compress_traffic_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "decompress_frac_of_peak": round(algorithmic / (reference["decompress_traffic_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    headline_row = codec.row(ms_c, ms_d, reference)
     del codec, x
     torch.cuda.empty_cache()
 
@@ -556,7 +612,7 @@ def main() -> int:
                 md = event_timed(c.decompress, r, torch)
                 if not args.no_verify:
                     c.verify()
-                row = c.row(mc, md)
+                row = c.row(mc, md, c.references(r))
                 del c, xo
                 torch.cuda.empty_cache()
             row = {"workload": other, **row}
@@ -565,12 +621,14 @@ def main() -> int:
         vgg_layers = vgg.pop("layers")
         rows.append({k: vgg[k] for k in ("workload", "tensors", "uncompressed_bytes", "compressed_bytes", "ratio",
                                            "algorithmic_bytes", "compress_ms", "decompress_ms",
-                                           "compress_frac", "decompress_frac")})
+                                           "compress_frac", "decompress_frac", "plain_kernel_same_traffic_ms",
+                                           "plain_kernel_frac")})
         result["per_workload"] = rows
         result["vgg_offload"] = {"pipeline": vgg["pipeline"], "cdma_model": vgg["cdma_model"],
                                  "layers": [{k: l[k] for k in ("layer", "uncompressed_bytes", "density", "ratio",
                                                                 "compress_ms", "decompress_ms", "compress_frac",
-                                                                "decompress_frac")} for l in vgg_layers]}
+                                                                "decompress_frac", "plain_kernel_same_traffic_ms")}
+                                            for l in vgg_layers]}
     if host is not None:
         result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu, windowed=args.windowed)
     print(json.dumps(result))

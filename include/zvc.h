@@ -106,6 +106,18 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
  * restores the default) and applies to the encoder calls that use it. */
 zvc_status zvc_workspace_set_lookback_patience(void* d_ws, unsigned polls, hipStream_t stream);
 
+/* Measurement aid, not part of the method: enqueues a plain streaming kernel
+ * that reads read_bytes at d_in and writes write_bytes at d_out (what it writes
+ * is a mix of what it read), both split evenly over one workgroup per 64 KB of
+ * the larger side (per 16 KB below 32 MB), with 16-byte non-temporal accesses.  Given the byte counts of
+ * a zvc_compress call (n*w in, the stream out) or of a zvc_decompress call (the
+ * mirror) it shows what the memory system does with that traffic when the
+ * kernel has nothing else to do: the same-run yardstick that the benchmark
+ * prints beside every codec time.  Pointers 16-byte aligned, byte counts
+ * multiples of 16 (else ZVC_E_ALIGN), ranges disjoint. */
+zvc_status zvc_reference_stream(const void* d_in, size_t read_bytes, void* d_out, size_t write_bytes,
+                                hipStream_t stream);
+
 /* Number of times, since zvc_workspace_init, that a waiting tile computed a
  * predecessor's count itself.  Synchronous 8-byte device-to-host copy; call it
  * after the stream has drained. */

@@ -1579,6 +1579,41 @@ __global__ __launch_bounds__(kThreads) void count_kernel(const unsigned char* __
     }
 }
 
+// Measurement aid, not part of the method: a plain streaming kernel that reads
+// read_chunks 16-byte chunks and writes write_chunks of them, split evenly over
+// the workgroups (up to 64 KB each way per workgroup, non-temporal accesses, all
+// of a thread's loads in flight together, stores that depend on the loads).  It
+// shows what this memory system does with the traffic of a codec call when
+// nothing else is asked of the kernel.  LOADS 16-byte loads per thread: 64 KB
+// per workgroup, or 16 KB for small transfers (more workgroups than CUs).
+template <int LOADS>
+__global__ __launch_bounds__(kThreads) void reference_stream_kernel(const uint4* __restrict__ in,
+                                                                    size_t read_chunks, uint4* __restrict__ out,
+                                                                    size_t write_chunks, unsigned read_per_group,
+                                                                    unsigned write_per_group) {
+    const size_t r0 = static_cast<size_t>(blockIdx.x) * read_per_group;
+    const size_t w0 = static_cast<size_t>(blockIdx.x) * write_per_group;
+    uint4 v[LOADS];
+    unsigned mix = blockIdx.x;
+#pragma unroll
+    for (int k = 0; k < LOADS; ++k) {
+        const unsigned i = threadIdx.x + k * kThreads;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (i < read_per_group && r0 + i < read_chunks) v[k] = load16_stream(in + r0 + i);
+    }
+#pragma unroll
+    for (int k = 0; k < LOADS; ++k) mix ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+#pragma unroll
+    for (int k = 0; k < LOADS; ++k) {
+        const unsigned i = threadIdx.x + k * kThreads;
+        if (i < write_per_group && w0 + i < write_chunks) {
+            uint4 d = v[k];
+            d.x ^= mix;
+            store16_stream(out + w0 + i, d);
+        }
+    }
+}
+
 // -------------------------------------------------------------- host helpers
 inline bool aligned_to(const void* p, size_t a) {
     return reinterpret_cast<uintptr_t>(p) % a == 0;
@@ -1929,6 +1964,26 @@ zvc_status zvc_workspace_set_lookback_patience(void* d_ws, unsigned polls, hipSt
     WsHeader* hdr = static_cast<WsHeader*>(d_ws);
     return hip_ok(launch(write_word_kernel, dim3(1), dim3(1), stream, &hdr->patience_plus_one,
                          static_cast<unsigned long long>(polls) + 1ull));
+}
+
+zvc_status zvc_reference_stream(const void* d_in, size_t read_bytes, void* d_out, size_t write_bytes,
+                                hipStream_t stream) {
+    if ((d_in == nullptr && read_bytes != 0) || (d_out == nullptr && write_bytes != 0)) return ZVC_E_ARG;
+    if (!aligned_to(d_in, 16) || !aligned_to(d_out, 16) || read_bytes % 16 != 0 || write_bytes % 16 != 0)
+        return ZVC_E_ALIGN;
+    if (ranges_overlap(d_in, read_bytes, d_out, write_bytes)) return ZVC_E_ARG;
+    const size_t larger = read_bytes > write_bytes ? read_bytes : write_bytes;
+    if (larger == 0) return ZVC_OK;
+    const bool small = larger < (size_t{32} << 20);
+    const size_t group_bytes = static_cast<size_t>(kThreads) * 16 * (small ? 4 : 16);     // 16 KB | 64 KB
+    const size_t groups = div_up(larger, group_bytes);
+    if (groups > 0x7FFFFFFFull) return ZVC_E_ARG;
+    const size_t read_chunks = read_bytes / 16, write_chunks = write_bytes / 16;
+    return hip_ok(launch(small ? reference_stream_kernel<4> : reference_stream_kernel<16>,
+                         dim3(static_cast<unsigned>(groups)), dim3(kThreads), stream,
+                         static_cast<const uint4*>(d_in), read_chunks, static_cast<uint4*>(d_out), write_chunks,
+                         static_cast<unsigned>(div_up(read_chunks, groups)),
+                         static_cast<unsigned>(div_up(write_chunks, groups))));
 }
 
 zvc_status zvc_workspace_self_help_count(const void* d_ws, uint64_t* h_count) {

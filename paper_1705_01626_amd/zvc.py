@@ -27,7 +27,7 @@ EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_prefetch", "zvc_workspace_set_lookback_patience", "zvc_workspace_self_help_count",
            "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream",
            "zvc_window_compress", "zvc_window_decompress", "zvc_compress_bounded",
-           "zvc_compress_static")
+           "zvc_compress_static", "zvc_reference_stream")
 
 _lib = None
 
@@ -89,6 +89,8 @@ def load() -> ctypes.CDLL:
     lib.zvc_prefetch.argtypes = [vp, u64, sz, ci, vp, sz, vp, vp, sz, vp, vp]
     lib.zvc_workspace_set_lookback_patience.restype = ci
     lib.zvc_workspace_set_lookback_patience.argtypes = [vp, ctypes.c_uint, vp]
+    lib.zvc_reference_stream.restype = ci
+    lib.zvc_reference_stream.argtypes = [vp, sz, vp, sz, vp]
     lib.zvc_workspace_self_help_count.restype = ci
     lib.zvc_workspace_self_help_count.argtypes = [vp, vp]
     _lib = lib
@@ -145,6 +147,13 @@ def zvc_window_check_stream(h_stream: torch.Tensor, nbytes: int, h_offsets: torc
 def zvc_workspace_set_lookback_patience(ws: torch.Tensor, polls: int, stream=None) -> None:
     _check(load().zvc_workspace_set_lookback_patience(ws.data_ptr(), int(polls), _stream_handle(stream)),
            "zvc_workspace_set_lookback_patience")
+
+
+def zvc_reference_stream(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int,
+                         stream=None) -> None:
+    """Enqueue the plain streaming kernel (measurement aid): read_bytes from src, write_bytes to dst."""
+    _check(load().zvc_reference_stream(src.data_ptr(), read_bytes, dst.data_ptr(), write_bytes,
+                                       _stream_handle(stream)), "zvc_reference_stream")
 
 
 def zvc_workspace_self_help_count(ws: torch.Tensor) -> int:
