@@ -72,8 +72,9 @@ typedef enum zvc_status {
     ZVC_E_CORRUPT = 7    /* a compressed stream is inconsistent with its stated size */
 } zvc_status;
 
-/* Human-readable name of a status code (static storage, never NULL). */
-const char* zvc_status_string(zvc_status st);
+/* Human-readable name of a status code (static storage, never NULL; any integer
+ * is accepted, unknown ones give a string that says so). */
+const char* zvc_status_string(int status);
 
 /* ---- pure host arithmetic (no GPU needed) -------------------------------- */
 

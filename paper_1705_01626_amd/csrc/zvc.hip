@@ -1879,8 +1879,8 @@ zvc_status static_scratch(void** ptr) {
 // ------------------------------------------------------------------ C ABI
 extern "C" {
 
-const char* zvc_status_string(zvc_status st) {
-    switch (st) {
+const char* zvc_status_string(int status) {
+    switch (status) {
         case ZVC_OK: return "ZVC_OK";
         case ZVC_E_ARG: return "ZVC_E_ARG: invalid argument";
         case ZVC_E_WIDTH: return "ZVC_E_WIDTH: element width must be 2 or 4 bytes";

@@ -66,3 +66,36 @@ def test_zvc_is_layout_independent_and_rle_is_not(oracle):
     assert ratio["fp32_nchw"] > 1.15 * ratio["fp32_chwn"]
     zvc_ratio = sizes["fp32_nchw"][2] / sizes["fp32_nchw"][0]
     assert zvc_ratio > ratio["fp32_nhwc"] and zvc_ratio > ratio["fp32_chwn"]
+
+
+@pytest.mark.gpu
+def test_ratio_by_layout_at_full_size(oracle):
+    """The layout comparison at the full 128x256x28x28 size (section 7.1, the
+    compression-ratio-by-layout figure: ZVC compresses equally well however the
+    zeros are arranged, a run-length code does not).  ZVC sizes come from the GPU
+    (zvc_compressed_size), RLE sizes from the numpy reference; prints the table."""
+    from paper_1705_01626_amd import zvc
+    from tests.gpu_util import say
+    variants = workloads.layout_variants(seed=0, device="cuda")
+    rows = {}
+    for name in ("fp32_nchw", "fp32_nhwc", "fp32_chwn", "fp16_nchw", "bf16_nchw"):
+        x = variants[name].contiguous()
+        n, w = x.numel(), x.element_size()
+        assert n == 128 * 256 * 28 * 28
+        ws = zvc.new_workspace(n, w, x.device)
+        d_bytes = torch.zeros(1, dtype=torch.int64, device=x.device)
+        say("ratio by layout: %s" % name)
+        zvc.zvc_compressed_size(x, d_bytes, ws)
+        gpu_bytes = int(d_bytes.item())
+        words = x.view(torch.int32 if w == 4 else torch.int16).cpu().numpy().view(np.uint32 if w == 4 else np.uint16).reshape(-1)
+        assert gpu_bytes == rle_ref.zvc_compressed_bytes(words)           # the size formula on the host
+        rows[name] = (n * w, gpu_bytes, rle_ref.rle_compressed_bytes(words, 4096))
+    print("\n[layout-ratio] layout      bytes        ZVC bytes   ZVC ratio   RLE bytes (4 KB windows)   RLE ratio")
+    for name, (ub, zb, rb) in rows.items():
+        print("[layout-ratio] %-10s %11d %11d   %8.3f   %11d                %8.3f" % (name, ub, zb, ub / zb, rb, ub / rb))
+    zvc_fp32 = {rows[k][1] for k in ("fp32_nchw", "fp32_nhwc", "fp32_chwn")}
+    assert len(zvc_fp32) == 1                                             # layout independent, to the byte
+    rle = {k: rows[k][0] / rows[k][2] for k in rows}
+    zr = rows["fp32_nchw"][0] / rows["fp32_nchw"][1]
+    assert rle["fp32_nchw"] > 1.15 * rle["fp32_nhwc"] and rle["fp32_nchw"] > 1.15 * rle["fp32_chwn"]
+    assert zr > rle["fp32_nhwc"] and zr > rle["fp32_chwn"]
