@@ -77,9 +77,9 @@ class Codec:
     to more than 512 MB, twice the Infinity Cache, so that no call finds its data
     cached by the previous one (`warm` keeps one set)."""
 
-    def __init__(self, x, torch, zvc, relu=False, windowed=False, warm=False, seed=0):
+    def __init__(self, x, torch, zvc, relu=False, windowed=False, warm=False, seed=0, window_bytes=4096):
         self.torch, self.zvc = torch, zvc
-        self.relu, self.windowed = relu, windowed
+        self.relu, self.windowed, self.window_bytes = relu, windowed, window_bytes
         dev = x.device
         x_in = x
         if relu:
@@ -89,7 +89,7 @@ class Codec:
         self.expect = x
         self.n, self.w = x.numel(), x.element_size()
         n, w = self.n, self.w
-        self.windows = zvc.zvc_window_count(n, w) if windowed else 0
+        self.windows = zvc.zvc_window_count(n, w, window_bytes) if windowed else 0
         self.ws = zvc.new_workspace(n, w, dev)
         self.d_bytes = torch.zeros(1, dtype=torch.int64, device=dev)
         copies = 1 if warm else max(1, -(-(512 << 20) // max(n * w, 1)))
@@ -112,7 +112,7 @@ class Codec:
         xi, comp, _, offsets = self.sets[self.turn_c % self.copies]
         self.turn_c += 1
         if self.windowed:
-            self.zvc.zvc_window_compress(xi, comp, offsets, self.d_bytes, self.ws)
+            self.zvc.zvc_window_compress(xi, comp, offsets, self.d_bytes, self.ws, window_bytes=self.window_bytes)
         elif self.relu:
             self.zvc.zvc_relu_compress(xi, comp, self.d_bytes, self.ws)
         else:
@@ -122,7 +122,8 @@ class Codec:
         _, comp, out, offsets = self.sets[self.turn_d % self.copies]
         self.turn_d += 1
         if self.windowed:
-            self.zvc.zvc_window_decompress(comp, self.nbytes, offsets, self.n, 0, self.windows, out)
+            self.zvc.zvc_window_decompress(comp, self.nbytes, offsets, self.n, 0, self.windows, out,
+                                           window_bytes=self.window_bytes)
         else:
             self.zvc.zvc_decompress(comp, self.nbytes, out, self.ws)
 
@@ -224,7 +225,7 @@ def cpu_info():
 
 
 def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool = False,
-                 windowed: bool = False):
+                 windowed: bool = False, window_bytes: int = 4096):
     """The oracle as it stands, single thread, on the same bytes: whole-tensor
     compress + decompress round trips until about `budget_s` seconds are spent.
     With `relu` the encoder is the oracle's fused ReLU + ZVC (ReLU into a
@@ -244,7 +245,7 @@ def cpu_baseline(host_bytes, n: int, w: int, budget_s: float = 10.0, relu: bool 
     while reps < 1 or (spent < budget_s and reps < 50):
         t0 = time.perf_counter()
         if windowed:
-            per = 1024 // w
+            per = window_bytes // w
             windows = (n + per - 1) // per
             offsets = np.zeros(windows + 1, dtype=np.uint64)
             lib.zvc_ref_window_compress(vp(host_bytes.ctypes.data), n, w, per, vp(comp.ctypes.data),
@@ -455,6 +456,9 @@ def main() -> int:
     ap.add_argument("--windowed", action="store_true",
                     help="time the paper-order windowed stream (zvc_window_compress / "
                          "zvc_window_decompress of all windows) instead of the planar one")
+    ap.add_argument("--window-bytes", type=int, default=4096,
+                    help="with --windowed: the window size, a power of two from 1024 to 65536 "
+                         "(default: the paper's 4 KB)")
     ap.add_argument("--warm", action="store_true",
                     help="reuse one set of buffers (tensors under 512 MB then stay in the 256 MB "
                          "Infinity Cache); by default the calls rotate over enough copies to exceed 512 MB")
@@ -470,6 +474,8 @@ def main() -> int:
               "see DESIGN.md for how it would shard); --gpus %d is refused" % args.gpus,
               file=sys.stderr)
         return 2
+    if args.window_bytes not in (1024 << k for k in range(7)):
+        raise SystemExit("bench.py: --window-bytes is a power of two from 1024 to 65536")
     if args.relu and args.windowed:
         raise SystemExit("bench.py: --relu and --windowed are separate modes")
 
@@ -495,8 +501,9 @@ def main() -> int:
     if args.relu:
         described += "; pre-activations (zeros replaced by negative draws), fused ReLU + ZVC encoder"
     if args.windowed:
-        described += "; paper-order stream in 1 KB windows with an offset table"
-    codec = Codec(x, torch, zvc, relu=args.relu, windowed=args.windowed, warm=args.warm, seed=args.seed)
+        described += "; paper-order stream in %d KB windows with an offset table" % (args.window_bytes >> 10)
+    codec = Codec(x, torch, zvc, relu=args.relu, windowed=args.windowed, warm=args.warm, seed=args.seed,
+                  window_bytes=args.window_bytes)
     n, w = codec.n, codec.w
 
     if args.counter_pass:
@@ -563,7 +570,7 @@ def main() -> int:
                    "compressed_bytes": codec.nbytes, "density": round(codec.nnz / n, 6),
                    "compression_ratio": round(uncompressed / codec.nbytes, 4), "seed": args.seed,
                    "encoder": "relu+zvc" if args.relu else "zvc",
-                   "stream": "windowed" if args.windowed else "planar",
+                   "stream": "windowed (%d-byte windows)" % args.window_bytes if args.windowed else "planar",
                    "buffers": "%d rotating set%s (%s)" % (codec.copies, "" if codec.copies == 1 else "s",
                                                            "warm" if args.warm else "cold inputs")},
         "compress_GBps": round(uncompressed / (ms_c * 1e-3) / 1e9, 2),
@@ -630,7 +637,8 @@ def main() -> int:
                                                                 "decompress_frac", "plain_kernel_same_traffic_ms")}
                                             for l in vgg_layers]}
     if host is not None:
-        result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu, windowed=args.windowed)
+        result["cpu_baseline"] = cpu_baseline(host, n, w, relu=args.relu, windowed=args.windowed,
+                                              window_bytes=args.window_bytes)
     print(json.dumps(result))
     return 0
 

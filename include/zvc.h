@@ -217,47 +217,63 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
 
 /* Section 5.1 appends a group's non-zero elements right after its mask, and the
  * DMA engine of section 6 works on windows of uncompressed data, each decodable
- * on its own (4 KB there; the window size does not change the stream's bytes).
- * The windowed stream is that order: window after window (1024 / w elements
- * each -- 1 KB, so that four lanes of a wave can each walk one window's masks --
- * the last one possibly shorter), inside a window group after group, for each
- * group its 32-bit mask (little-endian; for w = 2 it may fall on a 2-byte
- * boundary) and then its kept elements.  Windows are packed back to back, so
- * the stream has exactly the bytes of the planar one, 4*ceil(n/32) + w*nnz.
- * Beside it goes a table of zvc_window_count(n, w) + 1 byte offsets: window k
- * occupies [offsets[k], offsets[k+1]) and the last entry is the stream's size.
- * The table (this library's addition, not counted in the compressed size: 8
- * bytes per KB) makes any range of windows decodable without touching the rest. */
+ * on its own: 4 KB there, and section 7.1 reports that windows up to 64 KB make
+ * little difference.  The windowed stream is that order: window after window
+ * (window_bytes / w elements each, the last one possibly shorter), inside a
+ * window group after group, for each group its 32-bit mask (little-endian; for
+ * w = 2 it may fall on a 2-byte boundary) and then its kept elements.  Windows
+ * are packed back to back, so the stream has exactly the bytes of the planar
+ * one, 4*ceil(n/32) + w*nnz, and they are the same bytes whatever the window
+ * size.  Beside it goes a table of zvc_window_count(n, w, window_bytes) + 1 byte
+ * offsets: window k occupies [offsets[k], offsets[k+1]) and the last entry is
+ * the stream's size.  The table (this library's addition, not counted in the
+ * compressed size: 8 bytes per window) makes any range of windows decodable
+ * without touching the rest.  The table of a larger window size is every
+ * (larger / smaller)-th entry of a smaller one's, plus the final size.
+ *
+ * window_bytes is a power of two from ZVC_WINDOW_MIN_BYTES to
+ * ZVC_WINDOW_MAX_BYTES; anything else is ZVC_E_ARG (0 from the two size
+ * functions).  Decoding walks a window's masks one after the other, so small
+ * windows decode fastest; the encoder's speed does not depend on the size. */
+#define ZVC_WINDOW_MIN_BYTES ((size_t)1024)
+#define ZVC_WINDOW_MAX_BYTES ((size_t)65536)
+#define ZVC_WINDOW_PAPER_BYTES ((size_t)4096)   /* the window of section 6 */
 
-/* Number of windows for n elements of width w: ceil(n*w / 1024).  0 for a bad w. */
-size_t zvc_window_count(size_t n, int w);
+/* Elements per window: window_bytes / w.  0 for a bad w or window size. */
+size_t zvc_window_elements(int w, size_t window_bytes);
+
+/* Number of windows for n elements of width w: ceil(n*w / window_bytes).  0 for
+ * a bad w or window size. */
+size_t zvc_window_count(size_t n, int w, size_t window_bytes);
 
 /* Host-side consistency check of a windowed stream and its table, both in HOST
  * memory: ZVC_OK iff the table starts at 0, ends at `bytes`, and every window,
  * walked mask by mask (a mask, then as many elements as it has bits set), ends
  * exactly where the next one begins; the last mask has no bit set past n. */
 zvc_status zvc_window_check_stream(const void* h_stream, uint64_t bytes, const uint64_t* h_offsets,
-                                   size_t n, int w);
+                                   size_t n, int w, size_t window_bytes);
 
 /* Compress into the windowed stream.  d_out / out_cap / d_bytes / workspace as
- * for zvc_compress; d_offsets is a device array of zvc_window_count(n, w) + 1
- * 64-bit words (8-byte aligned, not overlapping the other buffers). */
-zvc_status zvc_window_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
-                               uint64_t* d_offsets, uint64_t* d_bytes, void* d_ws, size_t ws,
-                               hipStream_t stream);
+ * for zvc_compress; d_offsets is a device array of
+ * zvc_window_count(n, w, window_bytes) + 1 64-bit words (8-byte aligned, not
+ * overlapping the other buffers). */
+zvc_status zvc_window_compress(const void* d_in, size_t n, int w, size_t window_bytes, void* d_out,
+                               size_t out_cap, uint64_t* d_offsets, uint64_t* d_bytes, void* d_ws,
+                               size_t ws, hipStream_t stream);
 
 /* Decompress windows first_window .. first_window + num_windows - 1 of a
  * windowed stream of n elements (a partial prefetch).  d_stream points at the
  * START of the stream (aligned to w) and stream_bytes is the number of readable
- * bytes there; d_offsets is the whole table.  d_out receives the elements of
- * those windows only, i.e. it points at where element first_window * 1024 / w
- * of the tensor goes.  Needs no workspace.  The kernel reads nothing outside
- * [d_stream, d_stream + stream_bytes) and the table entries of the windows
- * asked for; what a damaged table or mask asks for beyond a window's bytes
- * decodes as zero.  ZVC_E_ARG if the range does not lie within the windows. */
+ * bytes there; d_offsets is the whole table, made for this window_bytes.  d_out
+ * receives the elements of those windows only, i.e. it points at where element
+ * first_window * window_bytes / w of the tensor goes.  Needs no workspace.  The
+ * kernel reads nothing outside [d_stream, d_stream + stream_bytes) and the
+ * table entries of the windows asked for; what a damaged table or mask asks for
+ * beyond a window's bytes decodes as zero.  ZVC_E_ARG if the range does not lie
+ * within the windows. */
 zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, const uint64_t* d_offsets,
-                                 size_t n, int w, size_t first_window, size_t num_windows,
-                                 void* d_out, hipStream_t stream);
+                                 size_t n, int w, size_t window_bytes, size_t first_window,
+                                 size_t num_windows, void* d_out, hipStream_t stream);
 
 /* Offload (section 3 and section 5.4: the activation map leaves GPU memory as
  * a compressed copy whose size is known on completion).  Compresses d_in into

@@ -746,6 +746,7 @@ struct EncoderArgs {
     size_t state_bytes;
     unsigned long long cap_values;   // bytes that may be written at `values`
     unsigned long long* offsets;   // windowed stream only: byte offset of every window, then the total
+    unsigned window_shift;         // windowed stream only: a window is 1 KB << window_shift of input
 };
 
 // Section 5.1 encoder.  One workgroup per tile; tile = workgroup id.  With
@@ -772,9 +773,11 @@ struct EncoderArgs {
 //      whatever did not fit before.
 //
 // WINDOWED selects the paper's own stream order (section 5.1: a group's
-// non-zeros are appended right after its mask) in windows of 1 KB of input,
-// packed back to back, plus a table with the byte offset of every window.  A
-// window is four chunks, so the only differences are where things go in the
+// non-zeros are appended right after its mask), packed back to back, plus a
+// table with the byte offset of every window of 1 KB << window_shift of input
+// (section 6 uses 4 KB and tries up to 64 KB).  The stream's bytes do not depend
+// on the window size: the kernel works in units of 1 KB, four chunks, and stores
+// the offset of every unit that begins a window.  The only differences are where things go in the
 // wave's queue -- a group's mask sits before the group's elements -- and that
 // masks leave with the values instead of going to a mask area.  The scan is the
 // same: a window's byte offset is 4 x (groups before it) + W x (kept elements
@@ -784,7 +787,7 @@ __global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a)
     using G = EncoderGeometry<W, CH, WV>;
     constexpr int CG = G::kChunkGroups;
     constexpr int kAhead = CH;                    // all of a wave's loads are in flight from the start (measured: 3-6 % over 8 KB at a time)
-    constexpr int kWindowChunks = 4;              // a window of the windowed stream: 1 KB of input
+    constexpr int kWindowChunks = 4;              // the windowed stream's unit: 1 KB of input
     static_assert(W == 2 || !SPLIT, "only 16-bit elements can sit at an odd half dword");
 
     __shared__ __align__(16) unsigned char s_stage[WV][G::kQueueBytes];
@@ -1050,9 +1053,11 @@ __global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a)
         });
         if (WINDOWED && lane < CH / kWindowChunks) {
             // the byte offset of every window that exists: its masks before it, its kept elements before it
-            const size_t window = wave_group0 / (kWindowChunks * CG) + lane;
-            if (wave_group0 + static_cast<size_t>(lane) * (kWindowChunks * CG) < a.num_groups)
-                a.offsets[window] = static_cast<unsigned long long>(run_begin - a.values) + window_local;
+            const size_t unit = wave_group0 / (kWindowChunks * CG) + lane;     // 1 KB of input
+            if (wave_group0 + static_cast<size_t>(lane) * (kWindowChunks * CG) < a.num_groups &&
+                (unit & ((size_t{1} << a.window_shift) - 1)) == 0)
+                a.offsets[unit >> a.window_shift] =
+                    static_cast<unsigned long long>(run_begin - a.values) + window_local;
         }
     }
 
@@ -1061,7 +1066,8 @@ __global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a)
         const unsigned long long total =
             4ull * a.num_groups + static_cast<unsigned long long>(W) * (exclusive + tile_total);
         *a.d_bytes = total;
-        if (WINDOWED) a.offsets[div_up(a.num_groups, kWindowChunks * CG)] = total;
+        if (WINDOWED)
+            a.offsets[div_up(a.num_groups, static_cast<size_t>(kWindowChunks * CG) << a.window_shift)] = total;
     }
 
     if (tile == a.num_tiles - 1 && wave == 0)
@@ -1377,139 +1383,178 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
 
 // Decoder of the windowed stream.  No scan and no pre-pass: the offset table
 // says where a window's bytes are, and a window decodes from its own bytes alone
-// (section 5.2: the popcount of a mask gives the offset of the next mask).  A
-// wave takes four consecutive windows (4 KB of output): it stages their bytes
-// in LDS, lanes 0..3 each walk the masks of one window one after the other --
-// the serial chain the paper's decoder has too, here 8 or 16 steps through LDS
-// -- and leave every mask and the position of its first element for the other
-// lanes, which then rebuild 16 bytes of output per load as in the planar
-// decoder.  Reads stay inside [0, stream_bytes) and inside the staged bytes
-// whatever the table and the masks say; what a damaged stream asks for beyond
-// that decodes as zero.
-constexpr int kWindowBytes = 1024;      // uncompressed bytes per window: one load of a wave
+// (section 5.2: the popcount of a mask gives the offset of the next mask).  The
+// kernel works in pieces of 4 KB of output (four 1 KB loads of a wave): it
+// stages the piece's bytes in LDS, a few lanes walk the masks one after the
+// other -- the serial chain the paper's decoder has too -- and leave every mask
+// and the position of its first element for the other lanes, which then rebuild
+// 16 bytes of output per load as in the planar decoder.
+//   windows of 1, 2 or 4 KB: a wave takes one piece; it holds 4, 2 or 1 windows,
+//     and lanes 0..3, 0..1 or 0 walk one window each (8..32 masks of 32-bit
+//     elements, twice that of 16-bit ones);
+//   windows of 8..64 KB: a wave takes one window and goes through its pieces
+//     in order; lane 0 walks, and where its walk ends the next piece begins.
+// Reads stay inside [0, stream_bytes) and inside the staged bytes whatever the
+// table and the masks say; what a damaged stream asks for beyond that decodes
+// as zero.
+constexpr int kWindowUnitBytes = 1024;  // one load of a wave; window sizes are 1 KB << shift
+constexpr unsigned kMaxWindowShift = 6; // 64 KB
 
 template <int W, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     const unsigned char* __restrict__ stream, unsigned long long stream_bytes,
     const unsigned long long* __restrict__ offsets, size_t n, size_t num_groups,
-    size_t first_window, size_t num_windows, unsigned char* __restrict__ out, bool interleave) {
+    size_t first_window, size_t num_windows, unsigned window_shift, unsigned char* __restrict__ out,
+    bool interleave) {
     constexpr int E = 16 / W;
     constexpr int LPG = 32 / E;
-    constexpr int GPL = kWaveSize / LPG;                    // masks per window: 8 | 16
-    constexpr int kStepGroups = kStageLoads * GPL;          // masks per wave: 32 | 64
-    constexpr int kWindowElems = GPL * 32;
-    constexpr unsigned kMaxBytes = kStageLoads * (kWindowBytes + 4 * GPL);
-    static_assert(kWindowElems * W == kWindowBytes, "a window is one load of a wave");
+    constexpr int GPL = kWaveSize / LPG;                    // masks per KB of output: 8 | 16
+    constexpr int kPieceGroups = kStageLoads * GPL;         // masks per piece: 32 | 64
+    constexpr int kUnitElems = GPL * 32;
+    constexpr unsigned kPieceBytes = kStageLoads * kWindowUnitBytes;
+    constexpr unsigned kMaxBytes = kPieceBytes + 4 * kPieceGroups;   // a piece with nothing dropped
+    static_assert(kUnitElems * W == kWindowUnitBytes, "1 KB of output is one load of a wave");
 
     __shared__ __align__(16) unsigned char s_stage[kWaves][kMaxBytes + 16];
-    __shared__ unsigned s_mask[kWaves][kStepGroups];
-    __shared__ unsigned s_first[kWaves][kStepGroups];      // LDS offset of the group's first stored element
+    __shared__ unsigned s_mask[kWaves][kPieceGroups];
+    __shared__ unsigned s_first[kWaves][kPieceGroups];     // LDS offset of the group's first stored element
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWaveSize - 1);
     const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
-    // first of the wave's windows: dealt out in a row or, as in the planar decoder,
-    // interleaved over the XCDs
-    const size_t quad = interleave ? (static_cast<size_t>(blockIdx.x / 8) * kWaves + wave) * 8 + blockIdx.x % 8
-                                   : static_cast<size_t>(blockIdx.x) * kWaves + wave;
-    const size_t local = quad * kStageLoads;
+    const unsigned shift_w = window_shift;
+    // windows in a piece (small windows) | pieces in a window (large ones)
+    const unsigned piece_windows = shift_w <= 2 ? kStageLoads >> shift_w : 1u;
+    const unsigned window_pieces = shift_w <= 2 ? 1u : 1u << (shift_w - 2);
+    const unsigned walker_groups = static_cast<unsigned>(kPieceGroups) / piece_windows;
+    // the wave's share: dealt out in a row or, as in the planar decoder, interleaved over the XCDs
+    const size_t share = interleave ? (static_cast<size_t>(blockIdx.x / 8) * kWaves + wave) * 8 + blockIdx.x % 8
+                                    : static_cast<size_t>(blockIdx.x) * kWaves + wave;
+    const size_t local = share * piece_windows;             // first of the wave's windows, within the range
     if (local >= num_windows) return;
     const size_t window0 = first_window + local;
     const unsigned windows_here =
-        num_windows - local < kStageLoads ? static_cast<unsigned>(num_windows - local) : kStageLoads;
+        num_windows - local < piece_windows ? static_cast<unsigned>(num_windows - local) : piece_windows;
+    const size_t units = div_up(num_groups, static_cast<size_t>(GPL));   // KBs of output in the tensor
 
-    // ---- the windows' bytes, clamped to what can be there
     const auto clamped = [&](size_t k) {
         const unsigned long long o = offsets[k];
         return o > stream_bytes ? stream_bytes : o;
     };
-    const unsigned long long lo = clamped(window0);
+    unsigned long long lo = clamped(window0);               // where the piece's bytes begin
     unsigned long long hi = clamped(window0 + windows_here);
     if (hi < lo) hi = lo;
-    const unsigned bytes = hi - lo > kMaxBytes ? kMaxBytes : static_cast<unsigned>(hi - lo);
-    const unsigned char* src = stream + lo;    // wave-uniform, aligned to W
-    const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
-    const unsigned limit = shift + bytes;
     unsigned char* stage = s_stage[wave];
-    {
-        static_assert(kMaxBytes + 16 <= kFetchSlots * kWaveSize * 16, "the windows fit the fetch slots");
-        uint4 fetched[kFetchSlots];
-        wave_fetch(fetched, src - shift, bytes != 0 ? limit : 0u, false, lane);
-        wave_commit(stage, fetched, limit, bytes != 0 ? limit : 0u, lane);
-    }
-    wave_lds_sync();
 
-    // ---- lanes 0..3: the serial walk over one window's masks each
-    if (lane < kStageLoads) {
-        const size_t window = window0 + lane;
-        const size_t group0 = window * GPL;
-        const unsigned valid_groups = static_cast<unsigned>(lane) >= windows_here || group0 >= num_groups ? 0u
-            : num_groups - group0 < GPL ? static_cast<unsigned>(num_groups - group0)
-                                        : static_cast<unsigned>(GPL);
-        unsigned p = limit;   // a window that is not there, or whose offset is off, reads nothing
-        if (valid_groups != 0) {
-            const unsigned long long o = clamped(window);
-            if (o >= lo && o - lo <= bytes) p = shift + static_cast<unsigned>(o - lo);
-        }
-        for (unsigned g = 0; g < static_cast<unsigned>(GPL); ++g) {
-            unsigned m = 0;
-            if (g < valid_groups && p + 4u <= limit) {
-                if (W == 4)
-                    m = *reinterpret_cast<const unsigned*>(stage + p);
-                else
-                    m = *reinterpret_cast<const unsigned short*>(stage + p) |
-                        (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(stage + p + 2)) << 16);
-            }
-            s_mask[wave][lane * GPL + g] = m;
-            s_first[wave][lane * GPL + g] = p + 4u;
-            p += 4u + W * __popc(m);
-        }
-    }
-    wave_lds_sync();
+    static_assert(kMaxBytes + 16 <= kFetchSlots * kWaveSize * 16, "a piece fits the fetch slots");
 
-    // ---- expand: load jj is window jj of the wave
-    const size_t elem0 = window0 * kWindowElems;                  // in the tensor
-    unsigned char* wout = out + local * kWindowBytes;             // these windows' output
-    const bool full = ALIGNED && windows_here == kStageLoads && elem0 + kStageLoads * kWindowElems <= n;
-#pragma unroll
-    for (int jj = 0; jj < kStageLoads; ++jj) {
-        if (static_cast<unsigned>(jj) >= windows_here) break;
-        // element within the wave's part
-        const unsigned in_step = static_cast<unsigned>((jj * kWaveSize + lane) * E);
-        const int gl = jj * GPL + lane / LPG;
-        const unsigned gm = s_mask[wave][gl];
-        const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
-        unsigned at = s_first[wave][gl] + W * __popc(gm & ((1u << bit0) - 1u));
-        const unsigned field = gm >> bit0;
-        unsigned d[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int c = 0; c < E; ++c) {
-            const bool set = ((field >> c) & 1u) != 0u && at + W <= limit;
-            const unsigned from = set ? at : shift;
-            if (W == 4) {
-                const unsigned v = *reinterpret_cast<const unsigned*>(stage + from);
-                d[c] = set ? v : 0u;
-            } else {
-                const unsigned v = *reinterpret_cast<const unsigned short*>(stage + from);
-                d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
-            }
-            at += ((field >> c) & 1u) ? W : 0;
+    for (unsigned piece = 0; piece < window_pieces; ++piece) {
+        const size_t unit0 = (window0 << shift_w) + static_cast<size_t>(piece) * kStageLoads;
+        if (unit0 >= units) break;
+        size_t units_left = units - unit0;
+        if (shift_w <= 2 && units_left > (static_cast<size_t>(windows_here) << shift_w))
+            units_left = static_cast<size_t>(windows_here) << shift_w;
+        const unsigned units_here = units_left < kStageLoads ? static_cast<unsigned>(units_left) : kStageLoads;
+
+        // ---- the piece's bytes, clamped to what can be there
+        const unsigned cur_bytes = hi - lo > kMaxBytes ? kMaxBytes : static_cast<unsigned>(hi - lo);
+        const unsigned char* src = stream + lo;    // wave-uniform, aligned to W
+        const unsigned cur_shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
+        const unsigned cur_limit = cur_shift + cur_bytes;
+        {
+            uint4 fetched[kFetchSlots];
+            wave_fetch(fetched, src - cur_shift, cur_bytes != 0 ? cur_limit : 0u, false, lane);
+            wave_commit(stage, fetched, cur_limit, cur_bytes != 0 ? cur_limit : 0u, lane);
         }
-        const size_t e0 = elem0 + in_step;
-        if (full || (ALIGNED && e0 + E <= n)) {
-            store16_stream(wout + in_step * W, make_uint4(d[0], d[1], d[2], d[3]));
-        } else {
+        wave_lds_sync();
+
+        // ---- the serial walk: one lane per window of the piece
+        unsigned p = cur_limit;   // a window that is not there, or whose offset is off, reads nothing
+        if (static_cast<unsigned>(lane) < piece_windows) {
+            const size_t group0 = unit0 * GPL + static_cast<size_t>(lane) * walker_groups;
+            const unsigned valid_groups =
+                static_cast<unsigned>(lane) >= windows_here || group0 >= num_groups ? 0u
+                : num_groups - group0 < walker_groups ? static_cast<unsigned>(num_groups - group0)
+                                                      : walker_groups;
+            if (valid_groups != 0) {
+                // a small window begins where the table says; a piece of a large one where the last walk ended
+                const unsigned long long o = piece == 0 ? clamped(window0 + lane) : lo;
+                if (o >= lo && o - lo <= cur_bytes) p = cur_shift + static_cast<unsigned>(o - lo);
+            }
+            for (unsigned g = 0; g < walker_groups; ++g) {
+                unsigned m = 0;
+                if (g < valid_groups && p + 4u <= cur_limit) {
+                    if (W == 4)
+                        m = *reinterpret_cast<const unsigned*>(stage + p);
+                    else
+                        m = *reinterpret_cast<const unsigned short*>(stage + p) |
+                            (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(stage + p + 2)) << 16);
+                }
+                s_mask[wave][lane * walker_groups + g] = m;
+                s_first[wave][lane * walker_groups + g] = p + 4u;
+                p += 4u + W * __popc(m);
+            }
+        }
+        wave_lds_sync();
+
+        // ---- a large window's next piece begins where lane 0's walk ended (never beyond the
+        // window).  (Asking for its bytes here, before this piece is expanded, measured no faster.)
+        const bool more = piece + 1 < window_pieces && unit0 + kStageLoads < units;
+        unsigned long long next_lo = lo;
+        if (more) {
+            const unsigned end = lane_value(p, 0);
+            const unsigned long long next = lo + ((end < cur_limit ? end : cur_limit) - cur_shift);
+            next_lo = next < hi ? next : hi;
+        }
+
+        // ---- expand: load jj is KB jj of the piece
+        const size_t elem0 = unit0 * kUnitElems;                                  // in the tensor
+        unsigned char* wout = out + ((local << shift_w) + static_cast<size_t>(piece) * kStageLoads) *
+                                        kWindowUnitBytes;                         // this piece's output
+        const bool full = ALIGNED && units_here == kStageLoads && elem0 + kStageLoads * kUnitElems <= n;
+#pragma unroll
+        for (int jj = 0; jj < kStageLoads; ++jj) {
+            if (static_cast<unsigned>(jj) >= units_here) break;
+            // element within the piece
+            const unsigned in_step = static_cast<unsigned>((jj * kWaveSize + lane) * E);
+            const int gl = jj * GPL + lane / LPG;
+            const unsigned gm = s_mask[wave][gl];
+            const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
+            unsigned at = s_first[wave][gl] + W * __popc(gm & ((1u << bit0) - 1u));
+            const unsigned field = gm >> bit0;
+            unsigned d[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int c = 0; c < E; ++c) {
-                if (e0 + c < n) {
-                    if (W == 4)
-                        reinterpret_cast<unsigned*>(wout)[in_step + c] = d[c];
-                    else
-                        reinterpret_cast<unsigned short*>(wout)[in_step + c] = static_cast<unsigned short>(
-                            (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
+                const bool set = ((field >> c) & 1u) != 0u && at + W <= cur_limit;
+                const unsigned from = set ? at : cur_shift;
+                if (W == 4) {
+                    const unsigned v = *reinterpret_cast<const unsigned*>(stage + from);
+                    d[c] = set ? v : 0u;
+                } else {
+                    const unsigned v = *reinterpret_cast<const unsigned short*>(stage + from);
+                    d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
+                }
+                at += ((field >> c) & 1u) ? W : 0;
+            }
+            const size_t e0 = elem0 + in_step;
+            if (full || (ALIGNED && e0 + E <= n)) {
+                store16_stream(wout + in_step * W, make_uint4(d[0], d[1], d[2], d[3]));
+            } else {
+#pragma unroll
+                for (int c = 0; c < E; ++c) {
+                    if (e0 + c < n) {
+                        if (W == 4)
+                            reinterpret_cast<unsigned*>(wout)[in_step + c] = d[c];
+                        else
+                            reinterpret_cast<unsigned short*>(wout)[in_step + c] = static_cast<unsigned short>(
+                                (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
+                    }
                 }
             }
         }
+        if (!more) break;
+        lo = next_lo;
+        wave_lds_sync();     // the expand's reads of the stage are done before it is overwritten
     }
 }
 
@@ -1615,6 +1660,14 @@ __global__ __launch_bounds__(kThreads) void reference_stream_kernel(const uint4*
 }
 
 // -------------------------------------------------------------- host helpers
+// log2(window_bytes / 1 KB) for the window sizes of the windowed stream (a power of
+// two from 1 KB to 64 KB), else -1.
+inline int window_shift_of(size_t window_bytes) {
+    for (unsigned k = 0; k <= kMaxWindowShift; ++k)
+        if (window_bytes == static_cast<size_t>(kWindowUnitBytes) << k) return static_cast<int>(k);
+    return -1;
+}
+
 inline bool aligned_to(const void* p, size_t a) {
     return reinterpret_cast<uintptr_t>(p) % a == 0;
 }
@@ -1697,9 +1750,9 @@ template <int W, int CH, int WV, bool SPLIT>
 hipError_t launch_compress_as(Encoder mode, hipStream_t stream, const unsigned char* in, size_t n,
                         unsigned* masks, unsigned char* values, ScanState st,
                         unsigned long long* d_bytes, unsigned tiles, size_t groups,
-                        unsigned long long cap_values, unsigned long long* offsets) {
+                        unsigned long long cap_values, unsigned long long* offsets, unsigned window_shift) {
     const EncoderArgs args{in, n, masks, values, st.hdr, st.counts, st.prefixes, d_bytes, tiles,
-                           groups, scan_state_bytes(tiles), cap_values, offsets};
+                           groups, scan_state_bytes(tiles), cap_values, offsets, window_shift};
     const dim3 grid(tiles), block(WV * kWaveSize);
     switch (mode) {
         case Encoder::kPlain:
@@ -1768,7 +1821,7 @@ hipError_t launch_decompress(int w, bool aligned, Args... args) {
 // of this call's tiles (the library's own scratch array, which no decoder uses).
 zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n, int w, void* d_out,
                          size_t out_cap, uint64_t* d_bytes, uint64_t* d_offsets, void* d_ws, size_t ws,
-                         hipStream_t stream, bool scan_state_only = false) {
+                         hipStream_t stream, bool scan_state_only = false, unsigned window_shift = 0) {
     if (w != 2 && w != 4) return ZVC_E_WIDTH;
     if (d_bytes == nullptr || ((d_in == nullptr || d_out == nullptr) && n != 0)) return ZVC_E_ARG;
     if (!aligned_to(d_in, static_cast<size_t>(w)) || !aligned_to(d_out, 4) ||
@@ -1802,7 +1855,7 @@ zvc_status compress_impl(Encoder mode, bool bounded, const void* d_in, size_t n,
                     mode == Encoder::kWindowed ? static_cast<unsigned char*>(d_out) : values,
                     scan_state(d_ws, tiles), out_bytes, static_cast<unsigned>(tiles), groups,
                     !bounded ? ~0ull : out_cap - (mode == Encoder::kWindowed ? 0 : 4 * groups),
-                    reinterpret_cast<unsigned long long*>(d_offsets)));
+                    reinterpret_cast<unsigned long long*>(d_offsets), window_shift));
 }
 
 // One event per host thread and GPU for ordering a copy stream after a compute
@@ -1924,12 +1977,13 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
 }
 
 zvc_status zvc_window_check_stream(const void* h_stream, uint64_t bytes, const uint64_t* h_offsets,
-                                   size_t n, int w) {
+                                   size_t n, int w, size_t window_bytes) {
     if (w != 2 && w != 4) return ZVC_E_WIDTH;
+    if (window_shift_of(window_bytes) < 0) return ZVC_E_ARG;
     if (h_offsets == nullptr || (h_stream == nullptr && bytes != 0)) return ZVC_E_ARG;
-    const size_t windows = zvc_window_count(n, w);
+    const size_t windows = zvc_window_count(n, w, window_bytes);
     const size_t groups = div_up(n, 32);
-    const size_t groups_per_window = kWindowBytes / static_cast<size_t>(w) / 32;
+    const size_t groups_per_window = window_bytes / static_cast<size_t>(w) / 32;
     const unsigned char* p = static_cast<const unsigned char*>(h_stream);
     if (h_offsets[0] != 0 || h_offsets[windows] != bytes) return ZVC_E_CORRUPT;
     for (size_t k = 0; k < windows; ++k) {
@@ -2044,44 +2098,55 @@ zvc_status zvc_compress_bounded(const void* d_in, size_t n, int w, int relu, voi
                          d_bytes, nullptr, d_ws, ws, stream);
 }
 
-size_t zvc_window_count(size_t n, int w) {
-    if (w != 2 && w != 4) return 0;
-    return div_up(n * static_cast<size_t>(w), kWindowBytes);
+size_t zvc_window_elements(int w, size_t window_bytes) {
+    if ((w != 2 && w != 4) || window_shift_of(window_bytes) < 0) return 0;
+    return window_bytes / static_cast<size_t>(w);
 }
 
-zvc_status zvc_window_compress(const void* d_in, size_t n, int w, void* d_out, size_t out_cap,
-                               uint64_t* d_offsets, uint64_t* d_bytes, void* d_ws, size_t ws,
-                               hipStream_t stream) {
+size_t zvc_window_count(size_t n, int w, size_t window_bytes) {
+    if ((w != 2 && w != 4) || window_shift_of(window_bytes) < 0) return 0;
+    return div_up(n * static_cast<size_t>(w), window_bytes);
+}
+
+zvc_status zvc_window_compress(const void* d_in, size_t n, int w, size_t window_bytes, void* d_out,
+                               size_t out_cap, uint64_t* d_offsets, uint64_t* d_bytes, void* d_ws,
+                               size_t ws, hipStream_t stream) {
     if (d_offsets == nullptr) return ZVC_E_ARG;
     if (!aligned_to(d_offsets, 8)) return ZVC_E_ALIGN;
+    const int shift = window_shift_of(window_bytes);
+    if (shift < 0) return ZVC_E_ARG;
     if (w == 2 || w == 4) {
-        const size_t table = 8 * (zvc_window_count(n, w) + 1);
+        const size_t table = 8 * (zvc_window_count(n, w, window_bytes) + 1);
         if (ranges_overlap(d_offsets, table, d_out, zvc_max_compressed_bytes(n, w)) ||
             ranges_overlap(d_offsets, table, d_in, n * static_cast<size_t>(w)))
             return ZVC_E_ARG;
     }
     return compress_impl(Encoder::kWindowed, false, d_in, n, w, d_out, out_cap, d_bytes, d_offsets, d_ws, ws,
-                         stream);
+                         stream, false, static_cast<unsigned>(shift));
 }
 
 zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, const uint64_t* d_offsets,
-                                 size_t n, int w, size_t first_window, size_t num_windows,
-                                 void* d_out, hipStream_t stream) {
+                                 size_t n, int w, size_t window_bytes, size_t first_window,
+                                 size_t num_windows, void* d_out, hipStream_t stream) {
     if (w != 2 && w != 4) return ZVC_E_WIDTH;
-    const size_t windows = zvc_window_count(n, w);
+    const int shift = window_shift_of(window_bytes);
+    if (shift < 0) return ZVC_E_ARG;
+    const size_t windows = zvc_window_count(n, w, window_bytes);
     if (first_window > windows || num_windows > windows - first_window) return ZVC_E_ARG;
     if (num_windows == 0) return ZVC_OK;
     if (d_stream == nullptr || d_offsets == nullptr || d_out == nullptr) return ZVC_E_ARG;
     if (!aligned_to(d_out, static_cast<size_t>(w)) || !aligned_to(d_stream, static_cast<size_t>(w)) ||
         !aligned_to(d_offsets, 8))
         return ZVC_E_ALIGN;
-    const size_t elems_per_window = kWindowBytes / static_cast<size_t>(w);
+    const size_t elems_per_window = window_bytes / static_cast<size_t>(w);
     const size_t last_elem = (first_window + num_windows) * elems_per_window < n
                                  ? (first_window + num_windows) * elems_per_window : n;
     const size_t out_bytes = (last_elem - first_window * elems_per_window) * static_cast<size_t>(w);
     if (ranges_overlap(d_stream, stream_bytes, d_out, out_bytes)) return ZVC_E_ARG;
+    // a wave takes 4 KB of output, or one window if that is more
+    const size_t wave_windows = shift <= 2 ? static_cast<size_t>(kStageLoads >> shift) : 1;
     // (a multiple of 8 workgroups for the interleaved order)
-    const size_t blocks = div_up(div_up(num_windows, static_cast<size_t>(kWaves) * kStageLoads), 8) * 8;
+    const size_t blocks = div_up(div_up(num_windows, static_cast<size_t>(kWaves) * wave_windows), 8) * 8;
     if (blocks > 0x7FFFFFFFull) return ZVC_E_ARG;
     const dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
     const unsigned char* in = static_cast<const unsigned char*>(d_stream);
@@ -2094,7 +2159,7 @@ zvc_status zvc_window_decompress(const void* d_stream, size_t stream_bytes, cons
     const auto kernel = w == 4 ? (al ? window_decode_kernel<4, true> : window_decode_kernel<4, false>)
                                : (al ? window_decode_kernel<2, true> : window_decode_kernel<2, false>);
     return hip_ok(launch(kernel, grid, block, stream, in, static_cast<unsigned long long>(stream_bytes), offs, n,
-                         groups, first_window, num_windows, out, interleave));
+                         groups, first_window, num_windows, static_cast<unsigned>(shift), out, interleave));
 }
 
 zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w, void* d_out,

@@ -20,12 +20,16 @@ STATUS_NAMES = ("ZVC_OK", "ZVC_E_ARG", "ZVC_E_WIDTH", "ZVC_E_CAPACITY", "ZVC_E_W
 (ZVC_OK, ZVC_E_ARG, ZVC_E_WIDTH, ZVC_E_CAPACITY, ZVC_E_WORKSPACE, ZVC_E_ALIGN, ZVC_E_HIP,
  ZVC_E_CORRUPT) = range(8)
 
+# window sizes of the windowed stream (ZVC_WINDOW_* of include/zvc.h): powers of two in between
+WINDOW_MIN_BYTES, WINDOW_PAPER_BYTES, WINDOW_MAX_BYTES = 1024, 4096, 65536
+
 # every symbol include/zvc.h declares
 EXPORTS = ("zvc_status_string", "zvc_mask_bytes", "zvc_max_compressed_bytes",
            "zvc_workspace_bytes", "zvc_check_stream", "zvc_workspace_init",
            "zvc_compressed_size", "zvc_compress", "zvc_decompress", "zvc_offload",
            "zvc_prefetch", "zvc_workspace_set_lookback_patience", "zvc_workspace_self_help_count",
-           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_check_stream",
+           "zvc_relu_compress", "zvc_relu_offload", "zvc_window_count", "zvc_window_elements",
+           "zvc_window_check_stream",
            "zvc_window_compress", "zvc_window_decompress", "zvc_compress_bounded",
            "zvc_compress_static", "zvc_reference_stream")
 
@@ -68,13 +72,15 @@ def load() -> ctypes.CDLL:
     lib.zvc_compress_static.restype = ci
     lib.zvc_compress_static.argtypes = [vp, sz, ci, vp, sz, vp, vp]
     lib.zvc_window_count.restype = sz
-    lib.zvc_window_count.argtypes = [sz, ci]
+    lib.zvc_window_count.argtypes = [sz, ci, sz]
+    lib.zvc_window_elements.restype = sz
+    lib.zvc_window_elements.argtypes = [ci, sz]
     lib.zvc_window_check_stream.restype = ci
-    lib.zvc_window_check_stream.argtypes = [vp, u64, vp, sz, ci]
+    lib.zvc_window_check_stream.argtypes = [vp, u64, vp, sz, ci, sz]
     lib.zvc_window_compress.restype = ci
-    lib.zvc_window_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, vp, sz, vp]
+    lib.zvc_window_compress.argtypes = [vp, sz, ci, sz, vp, sz, vp, vp, vp, sz, vp]
     lib.zvc_window_decompress.restype = ci
-    lib.zvc_window_decompress.argtypes = [vp, sz, vp, sz, ci, sz, sz, vp, vp]
+    lib.zvc_window_decompress.argtypes = [vp, sz, vp, sz, ci, sz, sz, sz, vp, vp]
     lib.zvc_relu_compress.restype = ci
     lib.zvc_relu_compress.argtypes = [vp, sz, ci, vp, sz, vp, vp, sz, vp]
     lib.zvc_compress_bounded.restype = ci
@@ -136,12 +142,13 @@ def zvc_check_stream(h_comp: torch.Tensor, nbytes: int, n: int, w: int) -> int:
 
 
 def zvc_window_check_stream(h_stream: torch.Tensor, nbytes: int, h_offsets: torch.Tensor, n: int,
-                            w: int) -> int:
+                            w: int, window_bytes: int = WINDOW_PAPER_BYTES) -> int:
     """Host-side consistency check of a windowed stream (CPU uint8 tensor) and its table (CPU
     int64 tensor).  Returns the status code, it does not raise."""
     assert h_stream.device.type == "cpu" and h_offsets.device.type == "cpu"
     assert h_stream.is_contiguous() and h_offsets.is_contiguous() and h_offsets.dtype == torch.int64
-    return int(load().zvc_window_check_stream(h_stream.data_ptr(), nbytes, h_offsets.data_ptr(), n, w))
+    return int(load().zvc_window_check_stream(h_stream.data_ptr(), nbytes, h_offsets.data_ptr(), n, w,
+                                              window_bytes))
 
 
 def zvc_workspace_set_lookback_patience(ws: torch.Tensor, polls: int, stream=None) -> None:
@@ -233,32 +240,40 @@ def zvc_compress_bounded(x: torch.Tensor, out: torch.Tensor, d_bytes: torch.Tens
                                        _stream_handle(stream)), "zvc_compress_bounded")
 
 
-def zvc_window_count(n: int, w: int) -> int:
-    return int(load().zvc_window_count(n, w))
+def zvc_window_count(n: int, w: int, window_bytes: int = WINDOW_PAPER_BYTES) -> int:
+    return int(load().zvc_window_count(n, w, window_bytes))
+
+
+def zvc_window_elements(w: int, window_bytes: int = WINDOW_PAPER_BYTES) -> int:
+    """Elements per window; 0 for a width or window size the library does not take."""
+    return int(load().zvc_window_elements(w, window_bytes))
 
 
 def zvc_window_compress(x: torch.Tensor, out: torch.Tensor, offsets: torch.Tensor,
-                        d_bytes: torch.Tensor, ws: torch.Tensor, stream=None) -> None:
+                        d_bytes: torch.Tensor, ws: torch.Tensor, stream=None,
+                        window_bytes: int = WINDOW_PAPER_BYTES) -> None:
     """Enqueue compression of x into the paper-order windowed stream `out` (uint8) and its
     offset table `offsets` (int64, zvc_window_count + 1 entries)."""
     n = x.numel()
-    if offsets.numel() < zvc_window_count(n, x.element_size()) + 1:
+    if zvc_window_elements(x.element_size(), window_bytes) != 0 and \
+            offsets.numel() < zvc_window_count(n, x.element_size(), window_bytes) + 1:
         raise ZvcError(ZVC_E_CAPACITY, "zvc_window_compress (offset table too small)")
-    _check(load().zvc_window_compress(x.data_ptr(), n, x.element_size(), out.data_ptr(), out.numel(),
-                                      offsets.data_ptr(), d_bytes.data_ptr(), ws.data_ptr(),
+    _check(load().zvc_window_compress(x.data_ptr(), n, x.element_size(), window_bytes, out.data_ptr(),
+                                      out.numel(), offsets.data_ptr(), d_bytes.data_ptr(), ws.data_ptr(),
                                       ws.numel(), _stream_handle(stream)), "zvc_window_compress")
 
 
 def zvc_window_decompress(comp: torch.Tensor, comp_bytes: int, offsets: torch.Tensor, n: int,
-                          first_window: int, num_windows: int, out: torch.Tensor, stream=None) -> None:
+                          first_window: int, num_windows: int, out: torch.Tensor, stream=None,
+                          window_bytes: int = WINDOW_PAPER_BYTES) -> None:
     """Enqueue decompression of a range of windows into `out` (the elements of those windows)."""
     w = out.element_size()
-    per = 1024 // w
+    per = zvc_window_elements(w, window_bytes)
     need = max(0, min(n, (first_window + num_windows) * per) - first_window * per)
     if out.numel() < need:
         raise ZvcError(ZVC_E_CAPACITY, "zvc_window_decompress (output holds %d elements, %d needed)"
                        % (out.numel(), need))
-    _check(load().zvc_window_decompress(comp.data_ptr(), comp_bytes, offsets.data_ptr(), n, w,
+    _check(load().zvc_window_decompress(comp.data_ptr(), comp_bytes, offsets.data_ptr(), n, w, window_bytes,
                                         first_window, num_windows, out.data_ptr(),
                                         _stream_handle(stream)), "zvc_window_decompress")
 

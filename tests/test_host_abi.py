@@ -140,24 +140,35 @@ def test_window_check_stream_on_host(oracle):
     damaged ones: a flipped presence bit, a shifted table entry, a wrong total, a bit past n."""
     rng = np.random.default_rng(3)
     for w in (2, 4):
-        per = 1024 // w
+      for window in (1024, 4096, 65536):
+        per = zvc.zvc_window_elements(w, window)
+        assert per == window // w
         for n in (0, 1, 33, per, per + 1, 5 * per + 77):
             dtype = np.uint32 if w == 4 else np.uint16
             x = rng.integers(0, 3, size=n).astype(dtype)
             s, offs = oracle.window_compress(x, w, per)
-            assert zvc.zvc_window_count(n, w) == offs.size - 1
+            assert zvc.zvc_window_count(n, w, window) == offs.size - 1
             t = torch.from_numpy(np.concatenate([s, np.zeros(16, np.uint8)]))
             o = torch.from_numpy(offs.astype(np.int64))
-            assert zvc.zvc_window_check_stream(t, s.size, o, n, w) == zvc.ZVC_OK
+            assert zvc.zvc_window_check_stream(t, s.size, o, n, w, window) == zvc.ZVC_OK
             if n:
                 t2 = t.clone()
                 t2[0] ^= 1
-                assert zvc.zvc_window_check_stream(t2, s.size, o, n, w) == zvc.ZVC_E_CORRUPT
-                assert zvc.zvc_window_check_stream(t, s.size + w, o, n, w) == zvc.ZVC_E_CORRUPT
+                assert zvc.zvc_window_check_stream(t2, s.size, o, n, w, window) == zvc.ZVC_E_CORRUPT
+                assert zvc.zvc_window_check_stream(t, s.size + w, o, n, w, window) == zvc.ZVC_E_CORRUPT
             if offs.size > 2:
                 o2 = o.clone()
                 o2[1] += w
-                assert zvc.zvc_window_check_stream(t, s.size, o2, n, w) == zvc.ZVC_E_CORRUPT
+                assert zvc.zvc_window_check_stream(t, s.size, o2, n, w, window) == zvc.ZVC_E_CORRUPT
+                # a table made for another window size is not this stream's table
+                if window < 65536:
+                    assert zvc.zvc_window_check_stream(t, s.size, o, n, w, window * 2) == zvc.ZVC_E_CORRUPT
+    # window sizes the library does not take
+    for window in (0, 1000, 512, 3072, 131072):
+        assert zvc.zvc_window_count(100, 4, window) == 0 and zvc.zvc_window_elements(4, window) == 0
+        assert zvc.zvc_window_check_stream(torch.zeros(4, dtype=torch.uint8), 4,
+                                           torch.zeros(2, dtype=torch.int64), 32, 4, window) == zvc.ZVC_E_ARG
+    assert zvc.zvc_window_elements(3, 4096) == 0
     assert zvc.zvc_window_check_stream(torch.zeros(4, dtype=torch.uint8), 4,
                                        torch.zeros(2, dtype=torch.int64), 32, 3) == zvc.ZVC_E_WIDTH
 
@@ -177,7 +188,7 @@ int main(void) {
     if (zvc_mask_bytes(65) != 12) return 1;
     if (zvc_max_compressed_bytes(65, 2) != 12 + 130) return 2;
     if (zvc_workspace_bytes(1000, 4) == 0 || zvc_workspace_bytes(1000, 3) != 0) return 3;
-    if (zvc_window_count(1025, 4) != 5) return 4;
+    if (zvc_window_count(1025, 4, ZVC_WINDOW_PAPER_BYTES) != 2 || zvc_window_elements(2, 1024) != 512) return 4;
     unsigned int stream[3] = {0x5u, 7u, 9u};             /* one group of 3 elements: mask 101b, two values */
     if (zvc_check_stream(stream, 12, 3, 4) != ZVC_OK) return 5;
     if (zvc_check_stream(stream, 8, 3, 4) != ZVC_E_CORRUPT) return 6;
