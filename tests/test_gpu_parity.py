@@ -294,3 +294,25 @@ def test_decoder_survives_garbage_stream(oracle):
             torch.cuda.synchronize()
         x = random_tensor(n, w, 0.4, seed=1)
         assert_parity(x, oracle, "after garbage", ws)
+
+
+@pytest.mark.parametrize("read_bytes,write_bytes", [(16, 16), (16, 0), (0, 4096), (16384 + 16, 48), (5 << 20, (3 << 20) + 16),
+                                                     ((40 << 20) + 1040, 13 << 20), (9 << 20, (33 << 20) + 16)])
+def test_reference_stream_kernel_stays_inside_its_buffers(read_bytes, write_bytes):
+    """The benchmark's yardstick kernel: it writes every 16-byte chunk of [0, write_bytes) and
+    nothing outside (guard bytes on both sides keep their value), whatever the two sizes are,
+    and leaves its input alone."""
+    guard = 4096
+    src = torch.randint(1, 255, (read_bytes + 16,), dtype=torch.uint8, device=DEV)
+    keep = src.clone()
+    dst = torch.full((guard + write_bytes + guard,), 0xA5, dtype=torch.uint8, device=DEV)
+    say("reference stream read=%d write=%d" % (read_bytes, write_bytes))
+    zvc.zvc_reference_stream(src, read_bytes, dst[guard:], write_bytes)
+    torch.cuda.synchronize()
+    assert torch.equal(src, keep)
+    assert bool((dst[:guard] == 0xA5).all()) and bool((dst[guard + write_bytes:] == 0xA5).all())
+    if write_bytes:
+        # a chunk whose 16 bytes all still hold the fill value was not written (the kernel writes a mix
+        # of its input and the workgroup's number: 16 bytes of 0xA5 would be a coincidence of 2^-128)
+        chunks = dst[guard: guard + write_bytes].view(-1, 16)
+        assert not bool((chunks == 0xA5).all(dim=1).any())

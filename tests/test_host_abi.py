@@ -108,6 +108,34 @@ def test_argument_errors_before_any_gpu_call(lib):
     assert lib.zvc_workspace_init(None, 4096, None) == zvc.ZVC_E_ARG
     assert lib.zvc_workspace_init(WS, 100, None) == zvc.ZVC_E_WORKSPACE
     assert lib.zvc_workspace_init(WS + 8, 4096, None) == zvc.ZVC_E_ALIGN
+    r = lib.zvc_reference_stream
+    assert r(None, 64, OUT, 64, None) == zvc.ZVC_E_ARG
+    assert r(IN, 64, None, 64, None) == zvc.ZVC_E_ARG
+    assert r(IN + 4, 64, OUT, 64, None) == zvc.ZVC_E_ALIGN
+    assert r(IN, 60, OUT, 64, None) == zvc.ZVC_E_ALIGN
+    assert r(IN, 64, OUT, 72, None) == zvc.ZVC_E_ALIGN
+    assert r(IN, 4096, IN + 1024, 4096, None) == zvc.ZVC_E_ARG  # overlap
+    assert r(IN, 0, OUT, 0, None) == zvc.ZVC_OK                  # nothing to do, nothing launched
+    q = lib.zvc_workspace_set_lookback_patience
+    assert q(None, 5, None) == zvc.ZVC_E_ARG
+    assert q(WS + 8, 5, None) == zvc.ZVC_E_ALIGN
+    t = lib.zvc_compress_static
+    assert t(IN, n, 3, OUT, cap, BY, None) == zvc.ZVC_E_WIDTH
+    assert t(IN, (zvc.STATIC_MAX_BYTES // w) + 1, w, OUT, 1 << 40, BY, None) == zvc.ZVC_E_WORKSPACE
+    wc = lib.zvc_window_compress
+    OFF = 0x60000000
+    assert wc(IN, n, w, 4096, OUT, cap, None, BY, WS, wsb, None) == zvc.ZVC_E_ARG
+    assert wc(IN, n, w, 4096, OUT, cap, OFF + 4, BY, WS, wsb, None) == zvc.ZVC_E_ALIGN
+    assert wc(IN, n, w, 5000, OUT, cap, OFF, BY, WS, wsb, None) == zvc.ZVC_E_ARG
+    assert wc(IN, n, w, 4096, OUT, cap - 1, OFF, BY, WS, wsb, None) == zvc.ZVC_E_CAPACITY
+    wd = lib.zvc_window_decompress
+    assert wd(OUT, cap, OFF, n, w, 4096, 0, 2, IN, None) == zvc.ZVC_E_ARG          # one window only
+    assert wd(OUT, cap, OFF, n, w, 1024, 3, 2, IN, None) == zvc.ZVC_E_ARG          # four windows of 1 KB
+    assert wd(OUT, cap, OFF, n, w, 1024, 4, 0, IN, None) == zvc.ZVC_OK             # empty range at the end
+    assert wd(OUT, cap, OFF, n, w, 100, 0, 1, IN, None) == zvc.ZVC_E_ARG
+    assert wd(OUT, cap, OFF, n, 8, 4096, 0, 1, IN, None) == zvc.ZVC_E_WIDTH
+    assert wd(OUT, cap, OFF + 4, n, w, 4096, 0, 1, IN, None) == zvc.ZVC_E_ALIGN
+    assert wd(OUT, cap, OFF, n, w, 4096, 0, 1, OUT + 64, None) == zvc.ZVC_E_ARG    # overlap
 
 
 def test_check_stream_on_host(oracle):
