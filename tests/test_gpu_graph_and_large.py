@@ -55,7 +55,7 @@ def test_graph_replays_match_eager(oracle):
         assert nbytes == expect.size
         assert np.array_equal(comp[:nbytes].cpu().numpy(), expect)
         assert torch.equal(out, x)
-        wexpect, woffsets = oracle.window_compress(host, w, 1024 // w)
+        wexpect, woffsets = oracle.window_compress(host, w, zvc.WINDOW_PAPER_BYTES // w)
         assert int(w_bytes.item()) == wexpect.size
         assert np.array_equal(wcomp[: wexpect.size].cpu().numpy(), wexpect)
         assert offsets.cpu().numpy().astype(np.uint64).tolist() == woffsets.tolist()

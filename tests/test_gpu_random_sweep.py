@@ -86,12 +86,13 @@ def test_random_sweep(oracle):
             torch.cuda.synchronize()
             assert np.array_equal(raw_bytes(out), host)
         else:
-            per = 1024 // w
+            window = 1024 << int(rng.integers(0, 7))            # 1 KB .. 64 KB
+            per = window // w
             expect, table = oracle.window_compress(host, w, per)
-            windows = zvc.zvc_window_count(n, w)
+            windows = zvc.zvc_window_count(n, w, window)
             comp = zvc.new_compressed_buffer(n, w, DEV)
             offsets = torch.zeros(windows + 1, dtype=torch.int64, device=DEV)
-            zvc.zvc_window_compress(x, comp, offsets, d_bytes, ws)
+            zvc.zvc_window_compress(x, comp, offsets, d_bytes, ws, window_bytes=window)
             assert int(d_bytes.item()) == expect.size
             assert np.array_equal(comp[:expect.size].cpu().numpy(), expect)
             assert offsets.cpu().numpy().astype(np.uint64).tolist() == table.tolist()
@@ -99,7 +100,7 @@ def test_random_sweep(oracle):
             count = int(rng.integers(1, windows - first + 1))
             part_elems = min(n - first * per, count * per)
             part = out[:part_elems]
-            zvc.zvc_window_decompress(comp, expect.size, offsets, n, first, count, part)
+            zvc.zvc_window_decompress(comp, expect.size, offsets, n, first, count, part, window_bytes=window)
             torch.cuda.synchronize()
             assert np.array_equal(raw_bytes(part), host[first * per * w:(first * per + part_elems) * w])
         # the elements around the output range are untouched
