@@ -1759,13 +1759,16 @@ zvc_status check_workspace(const void* d_ws, size_t ws, size_t n, int w) {
 
 // Shape of the encoder's tile: chunks per wave x waves per workgroup.  Each tile
 // costs a fixed few nanoseconds of chip-wide time (workgroup launch plus the
-// scan's state traffic), so large tensors use 64 KB tiles; smaller tensors use
-// smaller tiles so that every CU still gets several.  More waves with fewer
-// chunks each shorten a tile's serial work (tests, compaction, flush) at the
-// same tile size.  The limits are measured crossover points.
+// scan's state traffic), so large fp32 tensors use 64 KB tiles; smaller tensors
+// use smaller tiles so that every CU still gets several.  16-bit elements are
+// twice the vector work per byte, and the 32 KB tile's eight waves per SIMD
+// (against four) hide it better: 32 KB tiles measure up to 9 % faster than
+// 64 KB ones at 411 MB, 822 MB and 1.6 GB alike.  The limits are measured
+// crossover points (8 KB tiles, and 8 or 16 waves per tile, were no faster
+// at any size).
 struct TileShape {
-    int chunks;   // per wave: 8, 16, 32 or 64
-    int waves;    // per workgroup: 4, 8 or 16
+    int chunks;   // per wave: 16, 32 or 64
+    int waves;    // per workgroup
 };
 constexpr size_t kLargeTensorBytes = size_t{384} << 20;
 constexpr size_t kMediumTensorBytes = size_t{12} << 20;
@@ -1775,7 +1778,8 @@ static_assert(kMinShape.chunks * kMinShape.waves * kChunkBytes == kMinLoads * 16
 inline TileShape choose_shape(size_t n, int w, bool split) {
     if (split) return kMinShape;
     const size_t bytes = n * static_cast<size_t>(w);
-    return bytes >= kLargeTensorBytes ? TileShape{64, 4} : bytes >= kMediumTensorBytes ? TileShape{32, 4} : kMinShape;
+    return bytes >= kLargeTensorBytes && w == 4 ? TileShape{64, 4}
+         : bytes >= kMediumTensorBytes ? TileShape{32, 4} : kMinShape;
 }
 
 enum class Encoder { kPlain, kRelu, kWindowed };
@@ -1830,7 +1834,7 @@ hipError_t launch_compress(int w, TileShape shape, bool split, Args... args) {
     if (shape.chunks == C && shape.waves == V)                                  \
         return w == 4 ? launch_compress_as<4, C, V, false>(args...)             \
                       : launch_compress_as<2, C, V, false>(args...);
-    ZVC_SHAPE_CASE(64, 4)
+    if (shape.chunks == 64 && shape.waves == 4 && w == 4) return launch_compress_as<4, 64, 4, false>(args...);
     ZVC_SHAPE_CASE(32, 4)
     ZVC_SHAPE_CASE(16, 4)
 #undef ZVC_SHAPE_CASE
