@@ -1266,14 +1266,84 @@ __global__ __launch_bounds__(kThreads) void mask_prefix_kernel(
     if (tid == 0) hdr->finish_top.value = 0u;
 }
 
-// Section 5.2 decoder.  Every wave works on its own: it expands LOADS loads'
-// worth of output (LOADS x 1 KB), kStageLoads loads at a time.  For each such
-// step it knows from the pre-pass where the step's stored elements begin and
-// end, stages them in its LDS slice with aligned 16-byte loads (never past
-// values_avail elements: anything the masks ask for beyond that decodes as
-// zero), and every lane rebuilds 16 bytes of output per load from "bit ? next
-// stored element : 0".  Slots whose bit is clear read a valid dummy address and
-// select zero.
+// One step of the decoder, by one wave: 4 KB of output from `m` (lane i holds
+// the step's mask i, bits past n cleared) and the step's `step_total` stored
+// elements, which begin at element `first` of the value area.  Stages them in
+// the wave's LDS slice with aligned 16-byte loads (never past values_avail
+// elements: anything the masks ask for beyond that decodes as zero); every lane
+// then rebuilds 16 bytes of output per load from "bit ? next stored element :
+// 0".  Slots whose bit is clear read a valid dummy address and select zero.
+template <int W, bool ALIGNED>
+__device__ __forceinline__ void expand_step(unsigned char* stage, const unsigned char* __restrict__ values,
+                                            unsigned long long values_avail, unsigned long long first,
+                                            unsigned step_total, unsigned m, size_t wave_elem0, size_t n,
+                                            unsigned char* __restrict__ out, bool stream_values, int lane) {
+    using G = Geometry<W, kMinLoads>;
+    constexpr int E = G::kElemsPerLane;
+    constexpr int LPG = G::kLanesPerGroup;
+    constexpr int kStepMasks = kStageLoads * G::kGroupsPerLoad;   // 32 | 64 masks per step
+    const bool full_wave = ALIGNED && wave_elem0 + static_cast<size_t>(kStageLoads) * kWaveSize * E <= n;
+    const unsigned char* src = values + first * W;  // wave-uniform
+    const unsigned shift = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
+    unsigned long long readable = values_avail > first ? values_avail - first : 0ull;
+    if (readable > step_total) readable = step_total;
+    const unsigned end = shift + step_total * W;
+    const unsigned end_valid = shift + static_cast<unsigned>(readable) * W;
+    uint4 fetched[kFetchSlots];
+    wave_fetch(fetched, src - shift, readable != 0 ? end_valid : 0u, stream_values, lane);
+    wave_commit(stage, fetched, end, end_valid > shift ? end_valid : 0u, lane);
+    // stored elements of the step before each of its masks (lane i holds mask i)
+    const unsigned cnt = __popc(m);
+    unsigned incl = cnt;
+#pragma unroll
+    for (int off = 1; off < kStepMasks; off <<= 1) {
+        const unsigned t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    const unsigned before_mask = incl - cnt;
+    wave_lds_sync();
+#pragma unroll
+    for (int jj = 0; jj < kStageLoads; ++jj) {
+        const size_t e0 = wave_elem0 + (static_cast<size_t>(jj) * kWaveSize + lane) * E;
+        const int gl = jj * G::kGroupsPerLoad + lane / LPG;     // the lane's mask within the step
+        const unsigned gm = __shfl(m, gl);
+        const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
+        unsigned at = shift + W * (__shfl(before_mask, gl) + __popc(gm & ((1u << bit0) - 1u)));
+        const unsigned field = gm >> bit0;
+        unsigned d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int c = 0; c < E; ++c) {
+            const bool set = (field >> c) & 1u;
+            const unsigned from = set ? at : shift;
+            if (W == 4) {
+                const unsigned v = *reinterpret_cast<const unsigned*>(stage + from);
+                d[c] = set ? v : 0u;
+            } else {
+                const unsigned v = *reinterpret_cast<const unsigned short*>(stage + from);
+                d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
+            }
+            at += set ? W : 0;
+        }
+        if (full_wave || (ALIGNED && e0 + E <= n)) {
+            store16_stream(out + e0 * W, make_uint4(d[0], d[1], d[2], d[3]));
+        } else {
+#pragma unroll
+            for (int c = 0; c < E; ++c) {
+                if (e0 + c < n) {
+                    if (W == 4)
+                        reinterpret_cast<unsigned*>(out)[e0 + c] = d[c];
+                    else
+                        reinterpret_cast<unsigned short*>(out)[e0 + c] = static_cast<unsigned short>(
+                            (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
+                }
+            }
+        }
+    }
+}
+
+// Section 5.2 decoder.  Every wave works on its own: it expands one step, 4 KB
+// of output, and knows from the pre-pass where the step's stored elements begin
+// and end (expand_step does the rest).
 template <int W, int LOADS, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
@@ -1282,7 +1352,6 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
     const unsigned* __restrict__ chunk_total, size_t num_groups, bool stream_values, bool interleave) {
     using G = Geometry<W, LOADS>;
     constexpr int E = G::kElemsPerLane;
-    constexpr int LPG = G::kLanesPerGroup;
     constexpr int kStepMasks = kStageLoads * G::kGroupsPerLoad;   // 32 | 64 masks per step
     constexpr int kStepUnits = kStepMasks / kUnitMasks;           // 1 | 2
     constexpr int kSteps = G::kStageSteps;
@@ -1342,77 +1411,119 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(
         step_end[h] = unit_end[u + kStepUnits - 1];
     }
 
-    const bool full_wave = ALIGNED && wave_elem0 + static_cast<size_t>(LOADS) * kWaveSize * E <= n;
-    unsigned char* stage = s_stage[wave];
-    // the stored elements of every step are requested before the first is expanded
-    uint4 fetched[kSteps][kFetchSlots];
-    unsigned shift_of[kSteps], end_of[kSteps], end_valid_of[kSteps];
-#pragma unroll
-    for (int h = 0; h < kSteps; ++h) {
-        const unsigned step_total = step_end[h] - step_begin[h];
-        const unsigned long long first = before_chunk + step_begin[h];
-        const unsigned char* src = values + first * W;  // wave-uniform
-        shift_of[h] = static_cast<unsigned>(reinterpret_cast<uintptr_t>(src) & 15u);
-        unsigned long long readable = values_avail > first ? values_avail - first : 0ull;
-        if (readable > step_total) readable = step_total;
-        end_of[h] = shift_of[h] + step_total * W;
-        end_valid_of[h] = shift_of[h] + static_cast<unsigned>(readable) * W;
-        wave_fetch(fetched[h], src - shift_of[h], readable != 0 ? end_valid_of[h] : 0u, stream_values, lane);
-    }
-#pragma unroll
-    for (int h = 0; h < kSteps; ++h) {
-        const unsigned shift = shift_of[h];
-        wave_commit(stage, fetched[h], end_of[h], end_valid_of[h] > shift ? end_valid_of[h] : 0u, lane);
-        // stored elements of the step before each of its masks (lane i holds mask i)
-        const unsigned cnt = __popc(m[h]);
-        unsigned incl = cnt;
-#pragma unroll
-        for (int off = 1; off < kStepMasks; off <<= 1) {
-            const unsigned t = __shfl_up(incl, off);
-            if (lane >= off) incl += t;
-        }
-        const unsigned before_mask = incl - cnt;
-        wave_lds_sync();
-#pragma unroll
-        for (int jj = 0; jj < kStageLoads; ++jj) {
-            const size_t e0 =
-                wave_elem0 + (static_cast<size_t>(h * kStageLoads + jj) * kWaveSize + lane) * E;
-            const int gl = jj * G::kGroupsPerLoad + lane / LPG;     // the lane's mask within the step
-            const unsigned gm = __shfl(m[h], gl);
-            const unsigned bit0 = static_cast<unsigned>(lane % LPG) * E;
-            unsigned at = shift + W * (__shfl(before_mask, gl) + __popc(gm & ((1u << bit0) - 1u)));
-            const unsigned field = gm >> bit0;
-            unsigned d[4] = {0u, 0u, 0u, 0u};
-#pragma unroll
-            for (int c = 0; c < E; ++c) {
-                const bool set = (field >> c) & 1u;
-                const unsigned from = set ? at : shift;
-                if (W == 4) {
-                    const unsigned v = *reinterpret_cast<const unsigned*>(stage + from);
-                    d[c] = set ? v : 0u;
-                } else {
-                    const unsigned v = *reinterpret_cast<const unsigned short*>(stage + from);
-                    d[c >> 1] |= (set ? v : 0u) << (16 * (c & 1));
-                }
-                at += set ? W : 0;
-            }
-            if (full_wave || (ALIGNED && e0 + E <= n)) {
-                store16_stream(out + e0 * W, make_uint4(d[0], d[1], d[2], d[3]));
-            } else {
-#pragma unroll
-                for (int c = 0; c < E; ++c) {
-                    if (e0 + c < n) {
-                        if (W == 4)
-                            reinterpret_cast<unsigned*>(out)[e0 + c] = d[c];
-                        else
-                            reinterpret_cast<unsigned short*>(out)[e0 + c] = static_cast<unsigned short>(
-                                (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu);
-                    }
-                }
+    static_assert(kSteps == 1, "a wave expands one step");
+    expand_step<W, ALIGNED>(s_stage[wave], values, values_avail, before_chunk + step_begin[0],
+                            step_end[0] - step_begin[0], m[0], wave_elem0, n, out, stream_values, lane);
+}
+
+// The same decoder in one launch, for small tensors: no pre-pass.  A workgroup
+// expands 16 KB of output, in stream order.  Where its stored elements begin is
+// the number of set bits in all masks before its own, which it gets the way the
+// encoder's tiles get their offsets: it publishes the popcount of its own 128
+// (256) masks and runs the device-wide scan over the workgroups before it
+// (scan_exclusive_prefix; same scan state in the workspace, same clean-up by the
+// last workgroup, same self-help if a predecessor has not been dispatched).  A
+// workgroup knows its count after one small load, so the scan's chain is short;
+// below a few tens of megabytes one launch beats the pre-pass's extra kernel,
+// above that the pre-pass wins because its expand kernel touches no shared state.
+struct CountMaskTile {
+    const unsigned* masks;
+    size_t num_groups;
+    unsigned tail;                 // n % 32
+    int tile_masks;                // masks per workgroup: 128 | 256
+    // set bits in the masks of workgroup q, wave-uniform
+    __device__ unsigned operator()(unsigned q, int lane) const {
+        unsigned count = 0;
+        for (int i = lane; i < tile_masks; i += kWaveSize) {
+            const size_t g = static_cast<size_t>(q) * tile_masks + i;
+            if (g < num_groups) {
+                unsigned m = __builtin_nontemporal_load(masks + g);
+                if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;
+                count += __popc(m);
             }
         }
-        wave_lds_sync();
+        return wave_sum_small(count);
     }
+};
+
+template <int W, bool ALIGNED>
+__global__ __launch_bounds__(kThreads) void decompress_scan_kernel(
+    const unsigned* __restrict__ masks, const unsigned char* __restrict__ values,
+    unsigned long long values_avail, size_t n, unsigned char* __restrict__ out, WsHeader* hdr,
+    unsigned* counts, unsigned long long* prefixes, unsigned num_tiles, size_t state_bytes,
+    size_t num_groups, bool stream_values) {
+    using G = Geometry<W, kMinLoads>;
+    constexpr int E = G::kElemsPerLane;
+    constexpr int kStepMasks = kStageLoads * G::kGroupsPerLoad;   // masks per wave: 32 | 64
+    static_assert(G::kStageSteps == 1, "a wave expands one step");
+
+    __shared__ __align__(16) unsigned char s_stage[kWaves][G::kWaveStageBytes];
+    __shared__ unsigned s_wave_total[kWaves];
+    __shared__ unsigned s_arrive;                 // waves arrived << 24 | set bits so far
+    __shared__ unsigned long long s_prefix;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWaveSize - 1);
+    const int wave = static_cast<int>(uniform(static_cast<unsigned>(tid / kWaveSize)));
+    const unsigned tile = blockIdx.x;
+    if (tid == 0) s_arrive = 0u;
+    const size_t wave_elem0 = (static_cast<size_t>(tile) * kWaves + wave) * (static_cast<size_t>(kMinLoads) * kWaveSize * E);
+    const size_t wave_group0 = wave_elem0 / 32;
+    const unsigned tail = static_cast<unsigned>(n % 32);
+
+    // ---- the wave's masks (lane i holds mask i) and their set bits
+    unsigned m = 0;
+    {
+        const size_t g = wave_group0 + lane;
+        if (lane < kStepMasks && g < num_groups) {
+            m = masks[g];
+            if (g == num_groups - 1 && tail != 0) m &= (1u << tail) - 1u;   // bits past n never count
+        }
+    }
+    lds_barrier();                                // the cleared arrival word, after the load has been issued
+    const unsigned wave_total = wave_sum_small(__popc(m));
+
+    // ---- the workgroup's count, published by the wave that arrives last; the scan, by wave 0
+    unsigned arrived = 0;
+    if (lane == 0) {
+        s_wave_total[wave] = wave_total;
+        arrived = __hip_atomic_fetch_add(&s_arrive, (1u << 24) | wave_total, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WORKGROUP);
+    }
+    arrived = uniform(arrived);
+    const bool publisher = (arrived >> 24) == kWaves - 1;
+    if (publisher && lane == 0)
+        store32(counts + tile, kCountValid | ((arrived & 0xFFFFFFu) + wave_total));
+    if (wave == 0) {
+        unsigned long long ex = 0;
+        if (tile != 0) {
+            const CountMaskTile count_tile{masks, num_groups, tail, kWaves * kStepMasks};
+            ex = scan_exclusive_prefix(counts, prefixes, tile, lane, hdr, count_tile);
+        }
+        if (lane == 0) s_prefix = ex;
+    }
+    // the count has reached memory before any wave of the workgroup goes on (see finish_arrive)
+    if (publisher) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_barrier();
+    const unsigned long long exclusive = uniform(s_prefix);
+    unsigned wave_offset = 0, tile_total = 0;
+#pragma unroll
+    for (int v = 0; v < kWaves; ++v) {
+        const unsigned t = uniform(s_wave_total[v]);
+        if (v < wave) wave_offset += t;
+        tile_total += t;
+    }
+    if (wave == 0 && lane == 0) {
+        if (tile % kBlockTiles == kBlockTiles - 1)
+            store64(prefixes + tile / kBlockTiles, kPrefixValid | (exclusive + tile_total));
+        finish_arrive(hdr, tile);
+    }
+
+    if (wave_elem0 < n)
+        expand_step<W, ALIGNED>(s_stage[wave], values, values_avail, exclusive + wave_offset, wave_total, m,
+                                wave_elem0, n, out, stream_values, lane);
+
+    if (tile == num_tiles - 1 && wave == 0) finish_call(hdr, counts, num_tiles, lane, state_bytes);
 }
 
 // Decoder of the windowed stream.  No scan and no pre-pass: the offset table
@@ -1802,6 +1913,10 @@ hipError_t launch_compress_as(Encoder mode, hipStream_t stream, const unsigned c
     }
     return hipErrorInvalidValue;
 }
+
+// Tensors below this size decode in one launch (decompress_scan_kernel): measured 1-2.5 us
+// faster than pre-pass + expand up to 19 MB, slower from 26 MB up.
+constexpr size_t kScanDecoderBytes = size_t{16} << 20;
 
 // Tensors below this size never decode in the interleaved order (no gain there).
 inline bool interleaves(size_t n, int w) { return n * static_cast<size_t>(w) >= (size_t{64} << 20); }
@@ -2214,6 +2329,22 @@ zvc_status zvc_decompress(const void* d_comp, size_t comp_bytes, size_t n, int w
     const size_t tiles = div_up(tiles_for(n, w, kMinLoads), 8) * 8;
     if (tiles > 0x7FFFFFFFull) return ZVC_E_ARG;
     const size_t groups = div_up(n, 32);
+    const unsigned char* stream_values_at = static_cast<const unsigned char*>(d_comp) + 4 * groups;
+    const unsigned long long stored_avail = (comp_bytes - 4 * groups) / static_cast<size_t>(w);
+    if (n * static_cast<size_t>(w) < kScanDecoderBytes) {
+        // one launch: the workgroups find their offsets with the encoder's scan (its state is at
+        // the front of the workspace, zero between calls)
+        const size_t scan_tiles = tiles_for(n, w, kMinLoads);
+        const ScanState st = scan_state(d_ws, scan_tiles);
+        const bool stream_values = stored_avail >= n / 4 * 3;
+        const auto kernel = w == 4 ? (al ? decompress_scan_kernel<4, true> : decompress_scan_kernel<4, false>)
+                                   : (al ? decompress_scan_kernel<2, true> : decompress_scan_kernel<2, false>);
+        return hip_ok(launch(kernel, dim3(static_cast<unsigned>(scan_tiles)), dim3(kThreads), stream,
+                             static_cast<const unsigned*>(d_comp), stream_values_at, stored_avail, n,
+                             static_cast<unsigned char*>(d_out), st.hdr, st.counts, st.prefixes,
+                             static_cast<unsigned>(scan_tiles), scan_state_bytes(scan_tiles), groups,
+                             stream_values));
+    }
     const size_t chunks = div_up(groups, kChunkMasks);
     if (chunks > 0xFFFFFFFFull) return ZVC_E_ARG;
     // The pre-pass arrays need no reset.  They sit at the end of the workspace, whatever its

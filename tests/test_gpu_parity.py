@@ -228,6 +228,29 @@ def test_scan_wait_that_helps_itself(oracle):
     assert helped > 0
 
 
+def test_single_launch_decoder_scan_that_helps_itself(oracle):
+    """Tensors below 16 MB decode in one launch whose workgroups find their offsets with the
+    device-wide scan.  With zero patience on the decoder's workspace (the stream comes from a call
+    on another one) every wait computes the missing workgroup's popcount itself; the output must
+    not change, and the workspace must be clean for the next call."""
+    for w, n in ((4, 3999999), (2, 8000001), (4, 4194303), (4, 4194304), (2, 33)):   # up to the 16 MB limit and just past it
+        x = random_tensor(n, w, 0.37, seed=n)
+        res = assert_parity(x, oracle, "decoder input")
+        ws = zvc.new_workspace(n, w, DEV)
+        zvc.zvc_workspace_set_lookback_patience(ws, 0)
+        out = torch.empty_like(x)
+        out.view(torch.uint8).fill_(0x5A)
+        say("zero-patience decode n=%d w=%d" % (n, w))
+        zvc.zvc_decompress(res["comp"], res["bytes"], out, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.uint8), x.view(torch.uint8))
+        helped = zvc.zvc_workspace_self_help_count(ws)
+        say("self-help events while decoding: %d" % helped)
+        if n * w < (16 << 20) and n > 100000:
+            assert helped > 0
+        assert_parity(x, oracle, "the same workspace afterwards", ws)
+
+
 def test_self_help_is_rare_in_normal_runs(oracle):
     """Default patience: predecessors publish long before a waiting tile gives
     up.  How often a count is computed twice depends on dispatch order and on
@@ -274,7 +297,9 @@ def test_decoder_many_chunks_and_reuse(oracle):
     w = 4
     n_max = 4096 * 32 * 300 + 12345
     ws = zvc.new_workspace(n_max, w, DEV)
-    for n in (4096 * 32, 4096 * 32 + 1, 4096 * 32 * 2 - 1, n_max, 4096 * 32 * 7 + 31, 1000):
+    # (tensors below 16 MB decode in one launch, without the pre-pass: the sizes from 33 chunks up take it)
+    for n in (4096 * 32, 4096 * 32 + 1, 4096 * 32 * 2 - 1, n_max, 4096 * 32 * 7 + 31, 1000,
+              4096 * 32 * 33 - 1, 4096 * 32 * 40 + 5, 4096 * 32 * 32, 4096 * 32 * 32 - 1):
         x = random_tensor(n, w, 0.41, seed=n)
         assert_parity(x, oracle, "pre-pass chunks n=%d" % n, ws=ws)
 
@@ -283,7 +308,7 @@ def test_decoder_survives_garbage_stream(oracle):
     """Random bytes as a compressed stream: masks then claim any number of stored elements, but
     reads are clamped to comp_bytes and a step never stages more than it has room for, so the
     kernels finish normally; the workspace stays usable."""
-    for w, n in ((4, 700001), (2, 1300003)):
+    for w, n in ((4, 700001), (2, 1300003), (4, 6000011), (2, 9000001)):     # one launch | pre-pass + expand
         g = torch.Generator(device="cpu").manual_seed(n)
         cap = zvc.zvc_max_compressed_bytes(n, w)
         junk = torch.randint(0, 256, (cap,), generator=g, dtype=torch.uint8).to(DEV)
