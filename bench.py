@@ -438,7 +438,15 @@ def load_traffic(workload: str, direction: str):
     entry = table.get(workload)
     if not entry:
         return None, None
-    return entry[direction]["total"], entry.get("source")
+    source = entry.get("source")
+    measured_on = entry.get("kernel_source_sha1")
+    if measured_on:
+        import hashlib
+        with open(os.path.join(ROOT, "paper_1705_01626_amd", "csrc", "zvc.hip"), "rb") as f:
+            current = hashlib.sha1(f.read()).hexdigest()
+        source = "%s (counters read on %s kernel source)" % (
+            source, "the current" if current == measured_on else "an EARLIER version of the")
+    return entry[direction]["total"], source
 
 
 def main() -> int:
