@@ -996,6 +996,9 @@ __global__ __launch_bounds__(WV * kWaveSize) void compress_kernel(EncoderArgs a)
         // neighbour (which reads them with a DPP row shift) the high halves into the next mask.
 #pragma unroll
         for (int r = 0; r < G::kMaskRegs; ++r) {
+            // (a DPP read of a register needs two wait states after the instruction that wrote it;
+            // the compiler sees the lane writes above only as opaque statements)
+            asm volatile("s_nop 1" : "+v"(mask_reg[r]), "+v"(second_reg[r]));
             const unsigned first_prev =
                 static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(mask_reg[r]), 0x111, 0xF, 0xF, true));
             const unsigned second_prev =
