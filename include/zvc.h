@@ -98,7 +98,7 @@ zvc_status zvc_check_stream(const void* h_comp, uint64_t bytes, size_t n, int w)
 
 /* ---- scan tuning and diagnostics ------------------------------------------ */
 
-/* The device-wide scan of per-tile counts (the "offset to the next mask" of
+/* The device-wide scan of per-tile counts (where the next mask's elements go,
  * section 5.1) lets a tile wait for its predecessors' counts.  After `polls`
  * fruitless polls the waiting tile computes the missing count itself, so the
  * wait always ends.  Default 2000 (about a millisecond); 0 makes every wait

@@ -1,35 +1,35 @@
 // Zero-value compression (ZVC) for AMD gfx950 (wave64): kernels and C ABI.
 //
-// The operation is the one of the paper's section 5.1 ("Zero-value
-// compression"): one 32-bit presence mask per 32 consecutive elements plus the
-// non-zero elements packed in order.  The paper builds it as a fixed-function
-// pipeline beside the memory controllers (section 5.2); this file is a GPU
-// kernel design instead:
+// The operation is the one of the paper's section 5.1: one 32-bit presence mask
+// per 32 consecutive elements plus the non-zero elements packed in order.  The
+// paper builds it as a fixed-function pipeline beside the memory controllers
+// (section 5.2); this file is a GPU kernel design instead:
 //
 //   * one pass over the input.  A workgroup owns a tile of 16 to 64 KB of input;
-//     each lane loads 16 bytes at a time (fully coalesced), tests its elements
-//     for a non-zero bit pattern with integer compares, and the wave derives
-//     packed positions from ballots + mbcnt (the GPU form of the paper's
-//     per-sector prefix sum over mask bits);
-//   * the offset of a tile's first kept element in the packed stream -- the
-//     paper's "offset to the next mask", a serial chain in hardware -- is a
+//     each lane loads one dword at a time (a wave instruction covers 256
+//     contiguous bytes), so the 64-lane ballot of the zero test is two finished
+//     masks and its mbcnt the packed position of the lane's element (the GPU
+//     form of the paper's per-sector prefix sum over mask bits);
+//   * the offset of a tile's first kept element in the packed stream -- where
+//     the next mask goes, a serial chain in the paper's hardware -- is a
 //     device-wide exclusive scan of per-tile counts done in the same pass:
-//     every tile publishes its count, every 64th tile a running prefix, and a
+//     every tile publishes its count, every 256th tile a running prefix, and a
 //     tile adds the counts between the nearest published prefix and itself;
-//   * kept elements are staged by each wave in LDS in packed order and leave as
-//     aligned 16-byte stores; masks leave as one contiguous run per wave.
+//   * kept elements are staged by each wave in an LDS queue in packed order and
+//     leave as whole 128-byte lines; masks leave as one contiguous run per wave.
 //
 // Decompression: where a span's stored elements start depends on the masks
 // alone, so a small pre-pass over the masks computes it for every 32 masks; the
 // expand kernel's waves then work independently: each stages its packed run in
 // LDS with aligned 16-byte loads and rebuilds 16 bytes of output per lane from
-// "bit ? next stored element : zero".
+// "bit ? next stored element : zero".  Small tensors decode in one launch that
+// uses the encoder's scan instead of the pre-pass.
 //
 // Three variants share these kernels: a fused ReLU + ZVC encoder
 // (pre-activations in, stream of ReLU(x) out), an encoder that writes into a
 // buffer below the worst case and never past it (section 9: streams kept in GPU
-// memory), and the paper's own stream order ("mask, then its non-zeros") in
-// independently decodable 1 KB windows with an offset table.
+// memory), and the paper's own stream order (a group's mask, then its non-zeros)
+// in independently decodable windows of 1 KB to 64 KB with an offset table.
 
 #include "zvc.h"
 
@@ -57,17 +57,12 @@ constexpr int kMaxDevices = 64;                // GPUs per process that per-GPU 
 constexpr unsigned kDefaultPatience = 2000;   // polls a waiting tile makes before it computes a missing count itself
 constexpr int kPollSleep = 8;                 // s_sleep units (64 clocks each) between polls
 
-// A tile is LOADS 16-byte loads per lane: 256 * 16 * LOADS bytes of input.
+// The decoder's tile: LOADS 16-byte stores per lane, 256 * 16 * LOADS bytes of output.
 template <int W, int LOADS>
 struct Geometry {
-    static constexpr int kElemsPerLane = 16 / W;                 // per 16-byte load: 4 | 8
+    static constexpr int kElemsPerLane = 16 / W;                 // per 16-byte store: 4 | 8
     static constexpr int kLanesPerGroup = 32 / kElemsPerLane;    // lanes covering one mask: 8 | 4
-    static constexpr int kGroupsPerLoad = kWaveSize / kLanesPerGroup;  // masks per wave-load: 8 | 16
-    static constexpr int kTileBytes = kThreads * 16 * LOADS;
-    static constexpr int kTileElems = kTileBytes / W;
-    static constexpr int kTileGroups = kTileElems / 32;
-    // mask hand-off: load j's mask is kept by lane (j % kLanesPerGroup) of the group
-    static constexpr int kMaskRegs = (LOADS + kLanesPerGroup - 1) / kLanesPerGroup;
+    static constexpr int kGroupsPerLoad = kWaveSize / kLanesPerGroup;  // masks per KB of output: 8 | 16
     // per-wave LDS staging buffer: kStageLoads wave-loads plus alignment slack
     static constexpr int kStageSteps = LOADS / kStageLoads;
     // (16 bytes so the slice can mirror the destination's alignment)
@@ -219,19 +214,6 @@ __device__ inline unsigned wave_sum_small(unsigned v) {
     return lane_value(v, 0) + lane_value(v, 16) + lane_value(v, 32) + lane_value(v, 48);
 }
 
-// OR over each aligned group of LANES lanes (8 or 4), result in every lane of
-// the group.  DPP: swap within pairs, swap pairs within quads, then (8 lanes)
-// mirror the half-row; after the quad steps all lanes of a quad agree, so the
-// mirror pairs the two quads.
-template <int LANES>
-__device__ inline unsigned group_or(unsigned m) {
-    m |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(m), 0xB1, 0xF, 0xF, true));
-    m |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(m), 0x4E, 0xF, 0xF, true));
-    if (LANES == 8)
-        m |= static_cast<unsigned>(__builtin_amdgcn_update_dpp(0, static_cast<int>(m), 0x141, 0xF, 0xF, true));
-    return m;
-}
-
 // Streaming 16-byte accesses, for what a call touches exactly once: the
 // uncompressed tensor (read by the encoder, written by the decoder) and the
 // encoder's output.  The non-temporal hint keeps such data from displacing other
@@ -319,13 +301,6 @@ __device__ inline unsigned presence_bits(const uint4& v) {
 #pragma unroll
     for (int c = 0; c < 16 / W; ++c) bits |= (element_kept<W, RELU>(v, c) ? 1u : 0u) << c;
     return bits;
-}
-
-template <int W>
-__device__ inline unsigned element_of(const uint4& v, int c) {
-    const unsigned d[4] = {v.x, v.y, v.z, v.w};
-    if (W == 4) return d[c];
-    return (d[c >> 1] >> (16 * (c & 1))) & 0xFFFFu;
 }
 
 // A dword of a wave's LDS queue at any offset that is a multiple of W (with
@@ -462,7 +437,7 @@ __device__ inline void wave_commit(unsigned char* stage, const uint4 (&r)[kFetch
 }
 
 // Device-wide exclusive scan of the per-tile counts, single pass (the paper's
-// "offset to the next mask", section 5.1, for a whole tile at a time).
+// offset at which the next mask goes, section 5.1, for a whole tile at a time).
 //
 // Protocol.  Every tile publishes its own count (the wave of the tile that
 // finishes its zero tests last does).  The last tile of every block of 256 also
