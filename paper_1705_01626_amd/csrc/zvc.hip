@@ -1538,7 +1538,7 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
     constexpr unsigned kMaxBytes = kPieceBytes + 4 * kPieceGroups;   // a piece with nothing dropped
     static_assert(kUnitElems * W == kWindowUnitBytes, "1 KB of output is one load of a wave");
 
-    __shared__ __align__(16) unsigned char s_stage[kWaves][kMaxBytes + 16];
+    __shared__ __align__(16) unsigned char s_stage[kWaves][kMaxBytes + 32];   // shift < 16, then an empty mask
     __shared__ unsigned s_mask[kWaves][kPieceGroups];
     __shared__ unsigned s_first[kWaves][kPieceGroups];     // LDS offset of the group's first stored element
 
@@ -1589,6 +1589,15 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
             wave_fetch(fetched, src - cur_shift, cur_bytes != 0 ? cur_limit : 0u, false, lane);
             wave_commit(stage, fetched, cur_limit, cur_bytes != 0 ? cur_limit : 0u, lane);
         }
+        // an empty mask behind the staged bytes: what the walk reads once it has run out of them
+        if (lane == 0) {
+            if (W == 4) {
+                *reinterpret_cast<unsigned*>(stage + cur_limit) = 0u;
+            } else {
+                *reinterpret_cast<unsigned short*>(stage + cur_limit) = 0;
+                *reinterpret_cast<unsigned short*>(stage + cur_limit + 2) = 0;
+            }
+        }
         wave_lds_sync();
 
         // ---- the serial walk: one lane per window of the piece
@@ -1605,14 +1614,16 @@ __global__ __launch_bounds__(kThreads) void window_decode_kernel(
                 if (o >= lo && o - lo <= cur_bytes) p = cur_shift + static_cast<unsigned>(o - lo);
             }
             for (unsigned g = 0; g < walker_groups; ++g) {
-                unsigned m = 0;
-                if (g < valid_groups && p + 4u <= cur_limit) {
-                    if (W == 4)
-                        m = *reinterpret_cast<const unsigned*>(stage + p);
-                    else
-                        m = *reinterpret_cast<const unsigned short*>(stage + p) |
-                            (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(stage + p + 2)) << 16);
-                }
+                // every step waits for the one before, so the loop has no branch: a mask that is
+                // not there (past the window's groups, or past the staged bytes) is read from the
+                // empty one behind them
+                const unsigned at = g < valid_groups && p + 4u <= cur_limit ? p : cur_limit;
+                unsigned m;
+                if (W == 4)
+                    m = *reinterpret_cast<const unsigned*>(stage + at);
+                else
+                    m = *reinterpret_cast<const unsigned short*>(stage + at) |
+                        (static_cast<unsigned>(*reinterpret_cast<const unsigned short*>(stage + at + 2)) << 16);
                 s_mask[wave][lane * walker_groups + g] = m;
                 s_first[wave][lane * walker_groups + g] = p + 4u;
                 p += 4u + W * __popc(m);
