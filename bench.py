@@ -467,6 +467,8 @@ def main() -> int:
     ap.add_argument("--window-bytes", type=int, default=4096,
                     help="with --windowed: the window size, a power of two from 1024 to 65536 "
                          "(default: the paper's 4 KB)")
+    ap.add_argument("--bf16", action="store_true",
+                    help="convert the workload's tensor to bf16 first (the 16-bit path at that shape)")
     ap.add_argument("--warm", action="store_true",
                     help="reuse one set of buffers (tensors under 512 MB then stay in the 256 MB "
                          "Infinity Cache); by default the calls rotate over enough copies to exceed 512 MB")
@@ -503,9 +505,13 @@ def main() -> int:
             "data": "synthetic", "config": {"workload": "vgg_offload"}, "vgg_offload": r}))
         return 0
 
-    table = args.workload is None and not (args.no_table or args.relu or args.windowed or args.counter_pass)
+    table = args.workload is None and not (args.no_table or args.relu or args.windowed or args.counter_pass
+                                           or args.bf16)
     name = args.workload or HEADLINE
     x, described = make_workload(name, args.seed, dev)
+    if args.bf16:
+        x = x.to(torch.bfloat16)
+        described += "; converted to bf16 (16-bit elements)"
     if args.relu:
         described += "; pre-activations (zeros replaced by negative draws), fused ReLU + ZVC encoder"
     if args.windowed:
@@ -559,7 +565,9 @@ def main() -> int:
     # trace; the events around the call see the kernel plus one launch gap.  zvc_decompress
     # is two kernels (mask pre-pass + expand) and is reported beside it as a whole call.
     achieved = algorithmic / (ms_c_in_step * 1e-3) / 1e9
-    traffic, traffic_source = load_traffic(name, "compress")
+    # (the counters were read on the plain encoder of the workload as it is: no figure for the variants)
+    traffic, traffic_source = (None, None) if (args.relu or args.windowed or args.bf16) \
+        else load_traffic(name, "compress")
     result = {
         "metric": "ZVC compress+decompress GB/s (uncompressed bytes) and % of HBM peak",
         "value": round(2.0 * uncompressed / (ms_per_step * 1e-3) / 1e9, 2),
